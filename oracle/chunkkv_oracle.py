@@ -1,0 +1,193 @@
+"""CPU oracle for ChunkKV prefill-time KV-cache compression.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, float64 statement of what the compression path computes, written
+from the paper (ChunkKV, arXiv 2502.00299): Algorithm 1 (Section 3.2),
+Algorithm 2 (Section 3.3, layer-wise index reuse) and Algorithm 3 (Appendix
+A.5, the mask-based formulation).  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import it; the product path never does.  It
+shares no code with the HIP path.
+
+Every function works on ONE sequence (no batch dimension); heads are explicit.
+
+Readings taken where the paper is silent or its listings disagree
+(each is also listed in the design document):
+  R1  The listings write A = Q_obs K^T; the text calls A "attention scores" in
+      the H2O/SnapKV sense, so A is softmax(Q_obs K^T / sqrt(d)) row by row.
+  R2  A window row i (0-based, the query at position P+i) sees keys 0..P+i
+      (causal prefill attention); its softmax runs over exactly those keys.
+  R3  Only the P = L - w non-window columns are chunked and ranked; the window
+      is kept unconditionally (Algorithm 3 ORs the window into the mask;
+      Algorithm 1 appends it), so the budget counts non-window tokens.
+  R4  Exactly n_keep non-window tokens are kept: chunks are taken whole in rank
+      order and the last-ranked one is cut to its leading tokens (Algorithm 1's
+      truncation to L_max - w rows and the "size of the last chunk" sentence
+      of Section 3.2).
+  R5  The ragged last chunk is a candidate scored by the sum over its fewer
+      tokens (Algorithm 3, end = min((i+1)c, T_k)).
+  R6  Equal chunk scores rank the lower chunk index first.
+  R7  Grouped-query attention: the selection is per kv-head; a token's
+      importance is the plain sum of its probabilities over the w window rows
+      of all g query heads that share the kv-head (Algorithm 3 sums over q).
+  R8  Kept tokens keep their original order; the window comes last.
+
+Pins (tests/test_oracle_pins.py): rows of the softmax sum to one; invariance to
+adding a constant vector to every key; w = g = 1 reduces to a library softmax;
+identical keys give p = 1/(P+i+1) in closed form, which also fixes the chunk
+grid and the ragged tail; a one-hot key gives a closed form that fixes the
+scale 1/sqrt(d) and the query-head-to-kv-head map; brute-force enumeration of
+the token order for tiny P; c = 1 reduces to a stable library argsort; uniform
+scores keep tokens [0, n_keep); nesting of kept sets; identity at n_keep = P;
+R = 1 equals per-layer compression; R >= N reuses layer 0 everywhere.
+The paper prints no worked numeric example of this path, so parity on real
+prompts is unpinned; everything above is pinned by mathematics only.
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+def widen(x: np.ndarray) -> np.ndarray:
+    """Stored values to float64, exactly.  uint16 arrays are bf16 bit patterns."""
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+def n_chunks(P: int, c: int) -> int:
+    """C = ceil(P / c) (Algorithm 1; applied to the non-window columns, reading R3)."""
+    return (P + c - 1) // c
+
+
+def window_probabilities(q_rows: np.ndarray, k: np.ndarray, w: int, scale: Optional[float] = None):
+    """Softmax attention of the window rows of ONE kv-head (Algorithm 1, first
+    step, with readings R1 and R2).
+
+    q_rows: [g*w][d] float64, row r = (query head within the group)*w + i.
+    k:      [L][d]  float64.
+    Returns p [g*w][L] with p[r, j] = 0 for the keys row r cannot see.
+    """
+    L, d = k.shape
+    P = L - w
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    s = (q_rows @ k.T) * scale                      # logits, [g*w][L]
+    i_of_row = np.arange(q_rows.shape[0]) % w       # window position of each row
+    visible = np.arange(L)[None, :] <= (P + i_of_row)[:, None]
+    s = np.where(visible, s, -np.inf)
+    s = s - s.max(axis=1, keepdims=True)
+    e = np.exp(s)                                   # exp(-inf) = 0 for hidden keys
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def token_importance(q_obs: np.ndarray, k: np.ndarray, w: int, scale: Optional[float] = None) -> np.ndarray:
+    """Per-kv-head importance of every non-window token (reading R7).
+
+    q_obs: [Hq][w][d], k: [Hkv][L][d] (stored values or float64).  Returns [Hkv][P].
+    """
+    q_obs, k = widen(q_obs), widen(k)
+    Hq, Hkv = q_obs.shape[0], k.shape[0]
+    g = Hq // Hkv
+    L = k.shape[1]
+    P = L - w
+    out = np.zeros((Hkv, P))
+    for h in range(Hkv):
+        rows = q_obs[h * g:(h + 1) * g].reshape(g * w, -1)   # heads h*g .. h*g+g-1
+        p = window_probabilities(rows, k[h], w, scale)
+        out[h] = p[:, :P].sum(axis=0)
+    return out
+
+
+def chunk_sums(imp: np.ndarray, c: int) -> np.ndarray:
+    """Chunk scores: chunk i sums tokens i*c .. min((i+1)c, P)-1 (Algorithm 3's
+    chunk-score loop; reading R5 for the ragged tail).  imp: [..., P]."""
+    P = imp.shape[-1]
+    C = n_chunks(P, c)
+    out = np.zeros(imp.shape[:-1] + (C,))
+    for i in range(C):
+        out[..., i] = imp[..., i * c:min((i + 1) * c, P)].sum(axis=-1)
+    return out
+
+
+def score(q_obs: np.ndarray, k: np.ndarray, w: int, c: int, scale: Optional[float] = None):
+    """(chunk_scores [Hkv][C], token_importance [Hkv][P]) of one sequence."""
+    imp = token_importance(q_obs, k, w, scale)
+    return chunk_sums(imp, c), imp
+
+
+def chunk_topk(scores: np.ndarray, P: int, c: int, n_keep: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Selection of ONE (sequence, kv-head) from its chunk scores (Algorithm 1's
+    top-k step under readings R4-R6, R8).
+
+    The P non-window tokens are put in the order (chunk score descending, chunk
+    index ascending, position ascending); the first n_keep of them are kept.
+    Returned as ascending (chunk index, number of leading tokens kept) pairs.
+    """
+    C = n_chunks(P, c)
+    assert scores.shape == (C,)
+    assert 0 <= n_keep <= P
+    assert np.all(np.isfinite(scores))
+    rank = np.argsort(-scores, kind="stable")      # ties: lower index first
+    order = np.concatenate([np.arange(i * c, min((i + 1) * c, P)) for i in rank]) if C else np.zeros(0, int)
+    kept = np.sort(order[:n_keep])
+    chunks, lens = np.unique(kept // c, return_counts=True)
+    return chunks.astype(np.int32), lens.astype(np.int32)
+
+
+def kept_token_indices(sel_chunk: np.ndarray, sel_len: np.ndarray, L: int, w: int, c: int) -> np.ndarray:
+    """Token indices a selection keeps, ascending, window last (reading R8)."""
+    P = L - w
+    parts = [np.arange(int(ch) * c, int(ch) * c + int(n)) for ch, n in zip(sel_chunk, sel_len)]
+    parts.append(np.arange(P, L))
+    return np.concatenate(parts).astype(np.int64)
+
+
+def compact(k: np.ndarray, v: np.ndarray, sel_chunk: Sequence[np.ndarray], sel_len: Sequence[np.ndarray],
+            w: int, c: int):
+    """Gather of one sequence (Algorithm 1's index_select + concatenation).
+
+    k, v: [Hkv][L][d] in their stored type (copied verbatim, no arithmetic).
+    sel_chunk[h], sel_len[h]: selection of kv-head h.  Returns K', V' [Hkv][n_kept][d].
+    """
+    Hkv, L, _ = k.shape
+    ko, vo = [], []
+    for h in range(Hkv):
+        idx = kept_token_indices(sel_chunk[h], sel_len[h], L, w, c)
+        ko.append(k[h][idx])
+        vo.append(v[h][idx])
+    return np.stack(ko), np.stack(vo)
+
+
+def compress_layer(q_obs, k, v, w: int, c: int, n_keep: int, scale: Optional[float] = None):
+    """Algorithm 1 for one layer of one sequence: returns (K', V', selection, chunk_scores)."""
+    P = k.shape[1] - w
+    cs, _ = score(q_obs, k, w, c, scale)
+    sel = [chunk_topk(cs[h], P, c, n_keep) for h in range(k.shape[0])]
+    ko, vo = compact(k, v, [s[0] for s in sel], [s[1] for s in sel], w, c)
+    return ko, vo, sel, cs
+
+
+def compress_stack(q_obs_layers, k_layers, v_layers, w: int, c: int, n_keep: int, reuse: int,
+                   scale: Optional[float] = None):
+    """Algorithm 2: layer l recomputes its selection when l mod reuse == 0 and
+    otherwise gathers with the selection of layer floor(l/reuse)*reuse.
+
+    q_obs_layers[l] may be None for layers that do not recompute.
+    Returns (list of K', list of V', list of selections per reuse group).
+    """
+    assert reuse >= 1
+    P = k_layers[0].shape[1] - w
+    store = {}
+    k_out, v_out, groups = [], [], []
+    for l in range(len(k_layers)):
+        if l % reuse == 0:
+            cs, _ = score(q_obs_layers[l], k_layers[l], w, c, scale)
+            store[l] = [chunk_topk(cs[h], P, c, n_keep) for h in range(k_layers[l].shape[0])]
+            groups.append(store[l])
+        sel = store[(l // reuse) * reuse]
+        ko, vo = compact(k_layers[l], v_layers[l], [s[0] for s in sel], [s[1] for s in sel], w, c)
+        k_out.append(ko)
+        v_out.append(vo)
+    return k_out, v_out, groups

@@ -1,0 +1,300 @@
+"""Pins for the CPU oracle: each test checks it against something the paper or
+the mathematics fixes (closed forms, invariants, library special cases, brute
+force on tiny inputs), never against the oracle's own formula or the HIP path.
+The paper (ChunkKV, Algorithms 1-3) prints no worked numeric example of the
+compression step, so there are no paper values to compare with.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp, softmax
+
+from oracle import chunkkv_oracle as orc
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ----------------------------------------------------------------- S1-S2 softmax
+@pytest.mark.parametrize("g,w,L,d", [(1, 4, 37, 8), (3, 5, 64, 16), (4, 16, 130, 64)])
+def test_rows_sum_to_one_over_visible_keys(g, w, L, d):
+    r = rng(1)
+    q = r.standard_normal((g * w, d))
+    k = r.standard_normal((L, d))
+    p = orc.window_probabilities(q, k, w)
+    assert np.allclose(p.sum(axis=1), 1.0, atol=1e-12)
+    P = L - w
+    for row in range(g * w):
+        i = row % w
+        assert np.all(p[row, P + i + 1:] == 0.0)          # hidden keys carry no mass
+        assert np.all(p[row, :P + i + 1] > 0.0)
+
+
+def test_shift_invariance_of_keys():
+    # adding one vector to every key adds a per-row constant to the logits
+    r = rng(2)
+    q = r.standard_normal((2, 4, 16))   # Hq=2, w=4
+    k = r.standard_normal((1, 50, 16))
+    a = orc.token_importance(q, k, 4)
+    b = orc.token_importance(q, k + r.standard_normal(16)[None, None, :], 4)
+    assert np.allclose(a, b, rtol=1e-10, atol=1e-14)
+
+
+def test_single_query_reduces_to_library_softmax():
+    # w = 1, g = 1: the only window row sees all L keys -> textbook softmax(K q / sqrt(d))
+    r = rng(3)
+    d, L = 32, 77
+    q = r.standard_normal((1, 1, d))
+    k = r.standard_normal((1, L, d))
+    imp = orc.token_importance(q, k, 1)
+    ref = softmax((k[0] @ q[0, 0]) / math.sqrt(d))
+    assert np.allclose(imp[0], ref[:L - 1], rtol=1e-12)
+
+
+def test_identical_keys_closed_form_and_chunk_grid():
+    # all keys equal -> row i is uniform over its P+i+1 visible keys, whatever Q is;
+    # importance of every prefix token = g * sum_i 1/(P+i+1); chunk score = size * that
+    r = rng(4)
+    Hq, Hkv, w, d, L, c = 6, 2, 5, 16, 48, 10     # P = 43 -> chunks of 10,10,10,10,3
+    g = Hq // Hkv
+    P = L - w
+    q = r.standard_normal((Hq, w, d))
+    k = np.tile(r.standard_normal((Hkv, 1, d)), (1, L, 1))
+    cs, imp = orc.score(q, k, w, c)
+    per_tok = g * sum(1.0 / (P + i + 1) for i in range(w))
+    assert imp.shape == (Hkv, P)
+    assert np.allclose(imp, per_tok, rtol=1e-12)
+    sizes = np.array([10, 10, 10, 10, 3])
+    assert cs.shape == (Hkv, 5)
+    assert np.allclose(cs, sizes[None, :] * per_tok, rtol=1e-12)
+    # mass identity: chunk scores sum to the window rows' mass on the prefix
+    assert np.allclose(cs.sum(axis=1), g * sum(P / (P + i + 1) for i in range(w)), rtol=1e-12)
+
+
+def test_one_hot_key_closed_form_pins_scale_and_gqa_map():
+    # kv-head 1 has a single non-zero key kappa*u at j*; query head qh has beta_qh*u in
+    # every window row.  Logit of (qh, i) on j* is beta_qh*kappa/sqrt(d), zero elsewhere:
+    #   p = e^t / (e^t + P + i)   with t = beta_qh*kappa/sqrt(d).
+    # kv-head 0 has identical keys (uniform rows).  Heads 3,4,5 belong to kv-head 1.
+    Hq, Hkv, w, d, L = 6, 2, 3, 16, 40
+    g, P, jstar, kappa = 3, 37, 11, 4.0
+    u = np.zeros(d)
+    u[2] = 1.0
+    beta = np.array([0.5, 1.0, 1.5, 2.0, 2.5, 3.0])
+    q = beta[:, None, None] * u[None, None, :] * np.ones((Hq, w, 1))
+    k = np.zeros((Hkv, L, d))
+    k[0, :, :] = 0.3
+    k[1, jstar, :] = kappa * u
+    imp = orc.token_importance(q, k, w)
+    exp1 = sum(math.exp(beta[qh] * kappa / math.sqrt(d)) /
+               (math.exp(beta[qh] * kappa / math.sqrt(d)) + P + i)
+               for qh in (3, 4, 5) for i in range(w))
+    assert imp[1, jstar] == pytest.approx(exp1, rel=1e-12)
+    other = sum(1.0 / (math.exp(beta[qh] * kappa / math.sqrt(d)) + P + i)
+                for qh in (3, 4, 5) for i in range(w))
+    assert np.allclose(np.delete(imp[1], jstar), other, rtol=1e-12)
+    assert np.allclose(imp[0], g * sum(1.0 / (P + i + 1) for i in range(w)), rtol=1e-12)
+
+
+def test_window_row_i_sees_exactly_its_causal_keys():
+    # a huge key placed inside the window at P+2 is visible to rows i >= 2 only
+    w, d, L = 4, 8, 20
+    P = L - w
+    q = np.ones((1, w, d))
+    k = np.zeros((1, L, d))
+    k[0, P + 2, :] = 50.0
+    p = orc.window_probabilities(q[0], k[0], w)
+    assert np.allclose(p[0, :P + 1], 1.0 / (P + 1))
+    assert np.allclose(p[1, :P + 2], 1.0 / (P + 2))
+    assert p[2, P + 2] > 1 - 1e-12 and p[3, P + 2] > 1 - 1e-12
+
+
+def test_importance_matches_library_logsumexp_per_row():
+    # p[r, j] = exp(s_rj - logsumexp_r) with the library's logsumexp over the visible keys
+    r = rng(5)
+    Hq, Hkv, w, d, L = 4, 2, 3, 8, 21
+    g, P = 2, 18
+    q = r.standard_normal((Hq, w, d))
+    k = r.standard_normal((Hkv, L, d))
+    imp = orc.token_importance(q, k, w)
+    for h in range(Hkv):
+        acc = np.zeros(P)
+        for qh in range(h * g, (h + 1) * g):
+            for i in range(w):
+                s = k[h, :P + i + 1] @ q[qh, i] / math.sqrt(d)
+                acc += np.exp(s - logsumexp(s))[:P]
+        assert np.allclose(imp[h], acc, rtol=1e-11)
+
+
+def test_bf16_widening_is_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x3DCD], dtype=np.uint16)
+    vals = orc.widen(bits)
+    assert vals[0] == 1.0 and vals[1] == -1.0 and vals[3] == 0.0
+    assert vals[2] == 3.140625                      # 0x4049 = 1.5703125 * 2
+    assert vals[4] == 0.10009765625
+
+
+# ----------------------------------------------------------------- S4 selection
+def brute_force_kept(scores, P, c, n_keep):
+    """Enumerate tokens, sort by (chunk score desc, chunk index asc, position asc)."""
+    toks = sorted(range(P), key=lambda t: (-float(scores[t // c]), t // c, t))
+    return sorted(toks[:n_keep])
+
+
+def expand(sel_chunk, sel_len, c):
+    return [int(ch) * c + t for ch, n in zip(sel_chunk, sel_len) for t in range(int(n))]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_selection_matches_brute_force_on_tiny_inputs(seed):
+    r = rng(100 + seed)
+    P = int(r.integers(1, 25))
+    c = int(r.integers(1, 8))
+    C = (P + c - 1) // c
+    # few distinct values -> many exact ties
+    scores = r.integers(0, 4, size=C).astype(np.float64) / 4.0
+    for n_keep in range(P + 1):
+        ch, ln = orc.chunk_topk(scores, P, c, n_keep)
+        assert expand(ch, ln, c) == brute_force_kept(scores, P, c, n_keep)
+
+
+def test_chunk_size_one_is_stable_topk():
+    r = rng(7)
+    P = 200
+    imp = np.round(r.random(P), 2)          # ties present
+    for n_keep in (0, 1, 17, 100, 200):
+        ch, ln = orc.chunk_topk(imp, P, 1, n_keep)
+        ref = np.sort(np.argsort(-imp, kind="stable")[:n_keep])
+        assert np.array_equal(ch, ref) and np.all(ln == 1)
+
+
+@pytest.mark.parametrize("P,c,n_keep", [(43, 10, 25), (40, 8, 40), (7, 10, 3), (30, 7, 0)])
+def test_uniform_scores_keep_leading_tokens(P, c, n_keep):
+    C = (P + c - 1) // c
+    ch, ln = orc.chunk_topk(np.full(C, 0.5), P, c, n_keep)
+    assert expand(ch, ln, c) == list(range(n_keep))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_selection_invariants_and_nesting(seed):
+    r = rng(200 + seed)
+    P, c = int(r.integers(30, 400)), int(r.integers(2, 21))
+    C = (P + c - 1) // c
+    scores = r.random(C)
+    prev = set()
+    for n_keep in range(0, P + 1):
+        ch, ln = orc.chunk_topk(scores, P, c, n_keep)
+        assert int(ln.sum()) == n_keep
+        assert np.all(np.diff(ch) > 0)
+        natural = np.minimum(c, P - ch.astype(np.int64) * c)
+        assert np.all((ln >= 1) & (ln <= natural))
+        assert int(np.sum(ln < natural)) <= 1           # at most one truncated chunk
+        kept = set(expand(ch, ln, c))
+        assert prev <= kept                              # budget n_keep nests in n_keep+1
+        prev = kept
+
+
+def test_ragged_tail_selected_pulls_next_ranked_chunk():
+    # P=23, c=10: chunks of 10, 10, 3.  Tail ranks first; budget 13 = tail + whole chunk 1.
+    scores = np.array([0.1, 0.5, 0.9])
+    ch, ln = orc.chunk_topk(scores, 23, 10, 13)
+    assert list(ch) == [1, 2] and list(ln) == [10, 3]
+    ch, ln = orc.chunk_topk(scores, 23, 10, 10)          # tail (3) + 7 leading of chunk 1
+    assert list(ch) == [1, 2] and list(ln) == [7, 3]
+    ch, ln = orc.chunk_topk(scores, 23, 10, 14)          # spills one token into chunk 0
+    assert list(ch) == [0, 1, 2] and list(ln) == [1, 10, 3]
+
+
+# ----------------------------------------------------------------- S5 gather
+def test_gather_identity_and_window():
+    r = rng(9)
+    Hkv, L, d, w, c = 2, 53, 4, 5, 6
+    P = L - w
+    k = r.standard_normal((Hkv, L, d)).astype(np.float32)
+    v = r.standard_normal((Hkv, L, d)).astype(np.float32)
+    full = [orc.chunk_topk(np.arange(orc.n_chunks(P, c), dtype=float), P, c, P) for _ in range(Hkv)]
+    ko, vo = orc.compact(k, v, [s[0] for s in full], [s[1] for s in full], w, c)
+    assert ko.tobytes() == k.tobytes() and vo.tobytes() == v.tobytes()
+    none = [(np.zeros(0, np.int32), np.zeros(0, np.int32))] * Hkv
+    ko, vo = orc.compact(k, v, [s[0] for s in none], [s[1] for s in none], w, c)
+    assert np.array_equal(ko, k[:, P:]) and np.array_equal(vo, v[:, P:])
+    # chunks 1 (whole) and 4 (two leading tokens): tokens 6..11 and 24,25, then the window
+    ch, ln = np.array([1, 4], np.int32), np.array([6, 2], np.int32)
+    idx = orc.kept_token_indices(ch, ln, L, w, c)
+    assert list(idx) == [6, 7, 8, 9, 10, 11, 24, 25] + list(range(P, L))
+    ko, vo = orc.compact(k, v, [ch, ch], [ln, ln], w, c)
+    for h in range(Hkv):
+        assert np.array_equal(ko[h], np.concatenate([k[h, 6:12], k[h, 24:26], k[h, P:]]))
+        assert np.array_equal(vo[h], np.concatenate([v[h, 6:12], v[h, 24:26], v[h, P:]]))
+
+
+def test_gather_rows_are_verbatim_copies():
+    r = rng(10)
+    Hkv, L, d, w, c = 1, 40, 8, 4, 5
+    k = r.integers(0, 65536, size=(Hkv, L, d)).astype(np.uint16)   # arbitrary bf16 bit patterns, NaNs included
+    v = r.integers(0, 65536, size=(Hkv, L, d)).astype(np.uint16)
+    ch, ln = np.array([0, 3, 6], np.int32), np.array([5, 2, 5], np.int32)
+    ko, vo = orc.compact(k, v, [ch], [ln], w, c)
+    rows = list(range(0, 5)) + [15, 16] + list(range(30, 35)) + list(range(36, 40))
+    assert ko.shape == (1, len(rows), d)
+    assert np.array_equal(ko[0], k[0, rows]) and np.array_equal(vo[0], v[0, rows])
+
+
+# ----------------------------------------------------------------- S6 reuse
+def _stack(seed, N, Hq=4, Hkv=2, L=60, d=8, w=4):
+    r = rng(seed)
+    qs = [r.standard_normal((Hq, w, d)) for _ in range(N)]
+    ks = [r.standard_normal((Hkv, L, d)) for _ in range(N)]
+    vs = [r.standard_normal((Hkv, L, d)) for _ in range(N)]
+    return qs, ks, vs
+
+
+def test_reuse_one_equals_per_layer():
+    qs, ks, vs = _stack(11, 5)
+    w, c, n_keep = 4, 6, 20
+    ko, vo, groups = orc.compress_stack(qs, ks, vs, w, c, n_keep, 1)
+    assert len(groups) == 5
+    for l in range(5):
+        k1, v1, sel, _ = orc.compress_layer(qs[l], ks[l], vs[l], w, c, n_keep)
+        assert np.array_equal(ko[l], k1) and np.array_equal(vo[l], v1)
+
+
+@pytest.mark.parametrize("N,R", [(5, 2), (5, 3), (4, 7), (6, 6)])
+def test_reuse_groups_share_the_leader_selection(N, R):
+    qs, ks, vs = _stack(12, N)
+    w, c, n_keep = 4, 6, 20
+    ko, vo, groups = orc.compress_stack([q if l % R == 0 else None for l, q in enumerate(qs)],
+                                        ks, vs, w, c, n_keep, R)
+    assert len(groups) == (N + R - 1) // R
+    for l in range(N):
+        leader = (l // R) * R
+        _, _, sel, _ = orc.compress_layer(qs[leader], ks[leader], vs[leader], w, c, n_keep)
+        k1, v1 = orc.compact(ks[l], vs[l], [s[0] for s in sel], [s[1] for s in sel], w, c)
+        assert np.array_equal(ko[l], k1) and np.array_equal(vo[l], v1)
+        assert ko[l].shape == (2, n_keep + w, 8)
+
+
+def test_keep_everything_is_identity_through_the_stack():
+    qs, ks, vs = _stack(13, 3)
+    w, c = 4, 6
+    ko, vo, _ = orc.compress_stack(qs, ks, vs, w, c, 60 - w, 2)
+    for l in range(3):
+        assert np.array_equal(ko[l], ks[l]) and np.array_equal(vo[l], vs[l])
+
+
+def test_planted_span_is_found_when_strong():
+    # a strongly planted span must be among the kept chunks (sanity of the whole path)
+    r = rng(14)
+    Hq, Hkv, w, d, L, c = 2, 1, 4, 32, 200, 10
+    P = L - w
+    u = r.standard_normal(d)
+    u /= np.linalg.norm(u)
+    q = r.standard_normal((Hq, w, d)) + 6.0 * u
+    k = r.standard_normal((Hkv, L, d))
+    k[0, 70:80] += 6.0 * u
+    v = r.standard_normal((Hkv, L, d))
+    _, _, sel, cs = orc.compress_layer(q, k, v, w, c, 20)
+    assert 7 in list(sel[0][0]) and int(np.argmax(cs[0])) == 7
