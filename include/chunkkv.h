@@ -1,0 +1,118 @@
+/*
+ * chunkkv.h - C ABI of the MI355X (gfx950) ChunkKV prefill-time KV-cache compression library.
+ *
+ * The operations follow ChunkKV (arXiv 2502.00299): Algorithm 1 (Section 3.2: observation-window
+ * attention scores -> chunk scores -> top-k chunks -> index_select + window concatenation),
+ * Algorithm 3 (Appendix A.5: boundary handling, ragged last chunk, window always kept) and
+ * Algorithm 2 (Section 3.3: layer-wise index reuse).
+ *
+ * Conventions
+ *   L  sequence length (T_k in the paper)      w  observation window     P = L - w  candidate tokens
+ *   c  chunk size                              C = ceil(P / c) chunks    Hq / Hkv query / kv heads
+ *   g = Hq / Hkv                               d  head dim               n_keep  candidate tokens kept
+ *   n_kept = n_keep + w  (L_max in the paper)  R  reuse depth (N_reuse in the paper)
+ *
+ * Every pointer named "device" is GPU memory owned by the caller; the library never allocates,
+ * frees or synchronises.  All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ * the default stream).  Host arrays inside chunkkv_problem and the per-layer pointer tables are
+ * read before the call returns.  Inputs are never written; outputs must not alias inputs.
+ * Inputs containing NaN/Inf give undefined results (no fault).
+ *
+ * Every function returns CHUNKKV_OK (0) or a positive chunkkv_status; nothing is enqueued when an
+ * argument check fails.
+ */
+#ifndef CHUNKKV_H
+#define CHUNKKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CHUNKKV_OK = 0,
+  CHUNKKV_ERR_NULL = 1,        /* a required pointer is NULL                                     */
+  CHUNKKV_ERR_SHAPE = 2,       /* inconsistent sizes: w > L, n_keep > P, Hq % Hkv != 0, caps ... */
+  CHUNKKV_ERR_UNSUPPORTED = 3, /* head_dim / dtype / row count not compiled in                   */
+  CHUNKKV_ERR_WORKSPACE = 4,   /* workspace smaller than chunkkv_workspace_bytes()               */
+  CHUNKKV_ERR_LAUNCH = 5       /* the HIP runtime refused a launch                               */
+} chunkkv_status;
+
+typedef enum { CHUNKKV_F32 = 0, CHUNKKV_BF16 = 1 } chunkkv_dtype;
+
+/* One batch of sequences sharing head geometry.  K and V of a layer live in one buffer each; token t
+ * of kv-head h of sequence b starts at element  kv_base[b] + h*kv_stride_head + t*kv_stride_tok  and
+ * its d elements are contiguous.  Both [B][Hkv][L][d] and packed variable-length [sum L][Hkv][d] fit.
+ * Row starts must be 16-byte aligned.  Outputs use out_base / out_stride_* the same way with n_kept_b
+ * tokens per head.  Supported: head_dim 64 or 128; g*w <= 512; batch, heads, L limited only by int32. */
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim;
+  int32_t window, chunk;        /* w >= 1, c >= 1                                                  */
+  int32_t dtype;                /* chunkkv_dtype: storage type of Q, K, V and of K', V'            */
+  float softmax_scale;          /* 0 selects 1/sqrt(head_dim)                                      */
+  const int32_t *seqlen;        /* host[batch]   L_b >= w                                          */
+  const int32_t *n_keep;        /* host[batch]   0 <= n_keep_b <= L_b - w                          */
+  const int64_t *kv_base;       /* host[batch]   element offsets into K / V                        */
+  int64_t kv_stride_head, kv_stride_tok;
+  const int64_t *out_base;      /* host[batch]   element offsets into K' / V'                      */
+  int64_t out_stride_head, out_stride_tok;
+  int32_t sel_cap;              /* >= max_b ceil(n_keep_b / c) + 1 : row pitch of sel_chunk/sel_len */
+  int32_t score_cap;            /* >= max_b ceil(P_b / c)          : row pitch of chunk_scores      */
+} chunkkv_problem;
+
+/* Selection descriptor (the paper's kept-index set I_l, Algorithm 2), per (sequence, kv-head):
+ *   sel_count            number of entries
+ *   sel_chunk[0..count)  strictly ascending chunk indices
+ *   sel_len[0..count)    leading tokens kept of that chunk, 1 <= len <= size of the chunk
+ * The window [P, L) is implicit and always kept.  Entries past sel_count are left untouched.      */
+
+const char *chunkkv_status_string(int status);
+
+/* Bytes of device workspace the calls below need for this problem; n_layers = reuse = 1 for the
+ * single-layer calls.  Returns 0 if the problem is invalid.                                        */
+size_t chunkkv_workspace_bytes(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse);
+
+/* Algorithm 1, scoring steps (with the softmax the text implies): for every kv-head, the g*w window
+ * rows (window row i of a head attends keys 0..P+i) are soft-maxed over their visible keys, summed
+ * over rows into per-token importance for tokens < P, and summed per chunk.
+ *   q_obs             device [B][Hq][w][d], the last w queries of every head
+ *   k                 device, layout given by prob
+ *   chunk_scores      device float [B][Hkv][score_cap]; entries [0, C_b) written
+ *   token_importance  device float [B][Hkv][score_cap*c] or NULL; entries [0, P_b) written
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; f32 inputs in fp32.       */
+int chunkkv_score(const chunkkv_problem *prob, const void *q_obs, const void *k, float *chunk_scores,
+                  float *token_importance, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Algorithm 1, top-k step, with the exact-budget rule: chunks are ranked by (score descending, index
+ * ascending); whole chunks are taken in rank order and the last-ranked one is cut to its leading
+ * tokens so that exactly n_keep_b tokens are kept.  Scores must be finite; -0 counts as +0.
+ *   chunk_scores  device float [B][Hkv][score_cap]
+ *   sel_chunk, sel_len  device int32 [B][Hkv][sel_cap];  sel_count device int32 [B][Hkv]           */
+int chunkkv_chunk_topk(const chunkkv_problem *prob, const float *chunk_scores, int32_t *sel_chunk,
+                       int32_t *sel_len, int32_t *sel_count, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/* Algorithm 1, compression + concatenation: K'[h] = rows of K[h] named by the selection, in order,
+ * followed by the window rows [P, L); same for V.  Pure copies, bit-exact.  The selection must obey
+ * the descriptor rules above and keep exactly n_keep_b tokens (not checked on the device).         */
+int chunkkv_compact(const chunkkv_problem *prob, const void *k, const void *v, const int32_t *sel_chunk,
+                    const int32_t *sel_len, const int32_t *sel_count, void *k_out, void *v_out,
+                    void *stream);
+
+/* Algorithm 2: for l = 0..n_layers-1, layers with l % reuse == 0 are scored and selected; every layer
+ * is compacted with the selection of layer floor(l/reuse)*reuse.
+ *   q_obs, k, v, k_out, v_out   host arrays of n_layers device pointers (q_obs[l] may be NULL when
+ *                               l % reuse != 0)
+ *   sel_chunk, sel_len          device int32 [G][B][Hkv][sel_cap], G = ceil(n_layers / reuse)
+ *   sel_count                   device int32 [G][B][Hkv]                                            */
+int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse,
+                           const void *const *q_obs, const void *const *k, const void *const *v,
+                           void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
+                           int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHUNKKV_H */

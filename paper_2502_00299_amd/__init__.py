@@ -1,0 +1,20 @@
+"""MI355X-native ChunkKV prefill-time KV-cache compression (arXiv 2502.00299).
+
+The package is a thin binding over libchunkkv.so (hand-written HIP for gfx950 behind a C ABI, see
+include/chunkkv.h).  PyTorch only provides device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    BF16,
+    F32,
+    LIB_PATH,
+    SYMBOLS,
+    ChunkKVError,
+    Problem,
+    chunkkv_chunk_topk,
+    chunkkv_compact,
+    chunkkv_compress_stack,
+    chunkkv_score,
+    chunkkv_status_string,
+    chunkkv_workspace_bytes,
+    load_library,
+)

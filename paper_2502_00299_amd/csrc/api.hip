@@ -1,0 +1,298 @@
+// Host side of libchunkkv: argument checks, workspace plan and launch sequence of the four C-ABI calls.
+#include <math.h>
+#include <string.h>
+
+#include "internal.h"
+
+namespace ckv {
+namespace {
+
+constexpr int kTargetWorkgroups = 2048;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
+
+struct Plan {
+  ScoreGeom geom;
+  int n_leaders, rows_pad;
+  int tpw0, tpw1, max_split0;
+  int fuse_chunks;
+  size_t off_part, off_refs, off_scores, off_seloff, off_imp, total;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int check_problem(const chunkkv_problem *p, bool need_out) {
+  if (!p) return CHUNKKV_ERR_NULL;
+  if (!p->seqlen || !p->n_keep || !p->kv_base) return CHUNKKV_ERR_NULL;
+  if (need_out && !p->out_base) return CHUNKKV_ERR_NULL;
+  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->window < 1 || p->chunk < 1)
+    return CHUNKKV_ERR_SHAPE;
+  if (p->n_q_heads % p->n_kv_heads != 0) return CHUNKKV_ERR_SHAPE;
+  if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return CHUNKKV_ERR_SHAPE;
+  if (p->dtype != CHUNKKV_F32 && p->dtype != CHUNKKV_BF16) return CHUNKKV_ERR_UNSUPPORTED;
+  if (p->head_dim != 64 && p->head_dim != 128) return CHUNKKV_ERR_UNSUPPORTED;
+  const int64_t rows = (int64_t)(p->n_q_heads / p->n_kv_heads) * p->window;
+  ScoreGeom g;
+  if (rows > kMaxRows || !score_geometry(p->dtype, p->head_dim, (int)rows, &g)) return CHUNKKV_ERR_UNSUPPORTED;
+  const int esz = p->dtype == CHUNKKV_BF16 ? 2 : 4;
+  if (p->kv_stride_tok < p->head_dim || p->kv_stride_head < 0) return CHUNKKV_ERR_SHAPE;
+  if ((p->kv_stride_tok * esz) % 16 || (p->kv_stride_head * esz) % 16) return CHUNKKV_ERR_SHAPE;
+  if (need_out) {
+    if (p->out_stride_tok < p->head_dim || p->out_stride_head < 0) return CHUNKKV_ERR_SHAPE;
+    if ((p->out_stride_tok * esz) % 16 || (p->out_stride_head * esz) % 16) return CHUNKKV_ERR_SHAPE;
+  }
+  if (p->sel_cap < 1 || p->score_cap < 0) return CHUNKKV_ERR_SHAPE;
+  for (int b = 0; b < p->batch; ++b) {
+    const int64_t L = p->seqlen[b], nk = p->n_keep[b];
+    if (L < p->window || nk < 0 || nk > L - p->window) return CHUNKKV_ERR_SHAPE;
+    if (p->kv_base[b] < 0 || (p->kv_base[b] * esz) % 16) return CHUNKKV_ERR_SHAPE;
+    if (need_out && (p->out_base[b] < 0 || (p->out_base[b] * esz) % 16)) return CHUNKKV_ERR_SHAPE;
+    if (p->sel_cap < (nk + p->chunk - 1) / p->chunk + 1) return CHUNKKV_ERR_SHAPE;
+    if (p->score_cap < (L - p->window + p->chunk - 1) / p->chunk) return CHUNKKV_ERR_SHAPE;
+  }
+  return CHUNKKV_OK;
+}
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }
+
+// Workspace layout and key-range split; a pure function of (problem, n_layers, reuse).
+int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
+  if (n_layers < 1 || reuse < 1) return CHUNKKV_ERR_SHAPE;
+  const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
+  if (!score_geometry(p->dtype, p->head_dim, rows, &pl->geom)) return CHUNKKV_ERR_UNSUPPORTED;
+  pl->n_leaders = ceil_div(n_layers, reuse);
+  pl->rows_pad = pl->geom.nqw * pl->geom.wq * 32;
+  const int TK = pl->geom.tile_keys;
+  pl->fuse_chunks = p->chunk <= TK;
+  const int stride1 = pl->fuse_chunks ? (TK / p->chunk) * p->chunk : TK;
+  int64_t tiles0 = 0, tiles1 = 0;
+  for (int b = 0; b < p->batch; ++b) {
+    tiles0 += ceil_div(p->seqlen[b], TK);
+    tiles1 += ceil_div(p->seqlen[b] - p->window, stride1);
+  }
+  const int64_t heads = (int64_t)pl->n_leaders * p->n_kv_heads;
+  pl->tpw0 = (int)((tiles0 * heads + kTargetWorkgroups - 1) / kTargetWorkgroups);
+  pl->tpw1 = (int)((tiles1 * heads + kTargetWorkgroups - 1) / kTargetWorkgroups);
+  if (pl->tpw0 < 1) pl->tpw0 = 1;
+  if (pl->tpw1 < 1) pl->tpw1 = 1;
+  pl->max_split0 = 1;
+  for (int b = 0; b < p->batch; ++b) {
+    const int s = ceil_div(ceil_div(p->seqlen[b], TK), pl->tpw0);
+    if (s > pl->max_split0) pl->max_split0 = s;
+  }
+  const size_t problems = (size_t)pl->n_leaders * p->batch * p->n_kv_heads;
+  size_t off = 0;
+  pl->off_part = off;   off += align256(problems * pl->max_split0 * pl->rows_pad * sizeof(float2));
+  pl->off_refs = off;   off += align256(problems * pl->rows_pad * sizeof(float));
+  pl->off_scores = off; off += align256(problems * (size_t)p->score_cap * sizeof(float));
+  pl->off_seloff = off; off += align256(problems * (size_t)p->sel_cap * sizeof(int32_t));
+  pl->off_imp = off;
+  if (!pl->fuse_chunks) off += align256(problems * (size_t)p->score_cap * p->chunk * sizeof(float));
+  pl->total = off < 256 ? 256 : off;
+  return CHUNKKV_OK;
+}
+
+void fill_seq(SeqTable *t, const chunkkv_problem *p, int b0, int nb) {
+  memset(t, 0, sizeof(*t));
+  for (int i = 0; i < nb; ++i) {
+    t->seqlen[i] = p->seqlen[b0 + i];
+    t->n_keep[i] = p->n_keep[b0 + i];
+    t->kv_base[i] = p->kv_base[b0 + i];
+    t->out_base[i] = p->out_base ? p->out_base[b0 + i] : 0;
+  }
+}
+
+// Scores leader layers [g0, g0+ng) (pointer tables already gathered) for all sequences.
+int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, const void *const *k, int ng,
+              int leader0, float *chunk_scores, float *token_imp, int64_t imp_pitch, char *ws, hipStream_t s) {
+  const int TK = pl.geom.tile_keys;
+  for (int b0 = 0; b0 < p->batch; b0 += kMaxBatchPerLaunch) {
+    const int nb = p->batch - b0 < kMaxBatchPerLaunch ? p->batch - b0 : kMaxBatchPerLaunch;
+    ScoreArgs a;
+    memset(&a, 0, sizeof(a));
+    for (int i = 0; i < ng; ++i) { a.q[i] = q[i]; a.k[i] = k[i]; }
+    fill_seq(&a.seq, p, b0, nb);
+    a.leader0 = leader0; a.batch0 = b0; a.batch_total = p->batch;
+    a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads; a.window = p->window; a.chunk = p->chunk;
+    a.kv_stride_head = p->kv_stride_head; a.kv_stride_tok = p->kv_stride_tok;
+    const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.max_split = pl.max_split0; a.rows_pad = pl.rows_pad;
+    a.part_stats = (float2 *)(ws + pl.off_part);
+    a.refs = (float *)(ws + pl.off_refs);
+    a.chunk_scores = chunk_scores; a.score_cap = p->score_cap;
+    a.token_imp = token_imp; a.imp_pitch = imp_pitch;
+    a.fuse_chunks = pl.fuse_chunks;
+    if (!pl.fuse_chunks && !token_imp) { a.token_imp = (float *)(ws + pl.off_imp); a.imp_pitch = (int64_t)p->score_cap * p->chunk; }
+    int split0 = 1, split1 = 0;
+    const int stride1 = pl.fuse_chunks ? (TK / p->chunk) * p->chunk : TK;
+    for (int i = 0; i < nb; ++i) {
+      const int s0 = ceil_div(ceil_div(a.seq.seqlen[i], TK), pl.tpw0);
+      const int s1 = ceil_div(ceil_div(a.seq.seqlen[i] - p->window, stride1), pl.tpw1);
+      split0 = s0 > split0 ? s0 : split0;
+      split1 = s1 > split1 ? s1 : split1;
+    }
+    int rc;
+    a.tiles_per_wg = pl.tpw0;
+    rc = launch_score_pass(0, p->dtype, p->head_dim, pl.geom, a, dim3(split0, nb * p->n_kv_heads, ng), s);
+    if (rc) return rc;
+    rc = launch_stats_combine(a, ng, nb, TK, s);
+    if (rc) return rc;
+    a.tiles_per_wg = pl.tpw1;
+    rc = launch_score_pass(1, p->dtype, p->head_dim, pl.geom, a, dim3(split1, nb * p->n_kv_heads, ng), s);
+    if (rc) return rc;
+    if (!pl.fuse_chunks) {
+      rc = launch_chunk_sums(a, ng, nb, s);
+      if (rc) return rc;
+    }
+  }
+  return CHUNKKV_OK;
+}
+
+int run_topk(const chunkkv_problem *p, const float *chunk_scores, int n_groups, int32_t *sel_chunk,
+             int32_t *sel_len, int32_t *sel_count, int32_t *sel_off, hipStream_t s) {
+  for (int b0 = 0; b0 < p->batch; b0 += kMaxBatchPerLaunch) {
+    const int nb = p->batch - b0 < kMaxBatchPerLaunch ? p->batch - b0 : kMaxBatchPerLaunch;
+    TopkArgs a;
+    memset(&a, 0, sizeof(a));
+    fill_seq(&a.seq, p, b0, nb);
+    a.batch0 = b0; a.batch_total = p->batch; a.n_kv_heads = p->n_kv_heads; a.window = p->window; a.chunk = p->chunk;
+    a.chunk_scores = chunk_scores; a.score_cap = p->score_cap; a.sel_cap = p->sel_cap;
+    a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
+    const int rc = launch_topk(a, n_groups, nb, s);
+    if (rc) return rc;
+  }
+  return CHUNKKV_OK;
+}
+
+int run_compact(const chunkkv_problem *p, int n_layers, int reuse, const void *const *k, const void *const *v,
+                void *const *k_out, void *const *v_out, const int32_t *sel_chunk, const int32_t *sel_len,
+                const int32_t *sel_count, const int32_t *sel_off, hipStream_t s) {
+  const int esz = p->dtype == CHUNKKV_BF16 ? 2 : 4;
+  for (int l0 = 0; l0 < n_layers; l0 += kMaxLayersPerLaunch) {
+    const int nl = n_layers - l0 < kMaxLayersPerLaunch ? n_layers - l0 : kMaxLayersPerLaunch;
+    for (int b0 = 0; b0 < p->batch; b0 += kMaxBatchPerLaunch) {
+      const int nb = p->batch - b0 < kMaxBatchPerLaunch ? p->batch - b0 : kMaxBatchPerLaunch;
+      CompactArgs a;
+      memset(&a, 0, sizeof(a));
+      for (int i = 0; i < nl; ++i) {
+        a.k[i] = k[l0 + i]; a.v[i] = v[l0 + i]; a.k_out[i] = k_out[l0 + i]; a.v_out[i] = v_out[l0 + i];
+      }
+      fill_seq(&a.seq, p, b0, nb);
+      a.layer0 = l0; a.reuse = reuse; a.batch0 = b0; a.batch_total = p->batch;
+      a.n_kv_heads = p->n_kv_heads; a.window = p->window; a.chunk = p->chunk; a.elem_bytes = esz;
+      a.kv_stride_head = p->kv_stride_head; a.kv_stride_tok = p->kv_stride_tok;
+      a.out_stride_head = p->out_stride_head; a.out_stride_tok = p->out_stride_tok;
+      a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
+      a.sel_cap = p->sel_cap;
+      int max_entries = 0;
+      for (int i = 0; i < nb; ++i) {
+        const int nk = a.seq.n_keep[i];
+        int e = (nk > 0 ? ceil_div(nk, p->chunk) + 1 : 0) + ceil_div(p->window, p->chunk);
+        if (nk > 0 && e - ceil_div(p->window, p->chunk) > p->sel_cap) e = p->sel_cap + ceil_div(p->window, p->chunk);
+        max_entries = e > max_entries ? e : max_entries;
+      }
+      const int rc = launch_compact(p->head_dim * esz, a, nl, nb, max_entries, s);
+      if (rc) return rc;
+    }
+  }
+  return CHUNKKV_OK;
+}
+
+}  // namespace
+}  // namespace ckv
+
+using namespace ckv;
+
+extern "C" {
+
+const char *chunkkv_status_string(int status) {
+  switch (status) {
+    case CHUNKKV_OK: return "ok";
+    case CHUNKKV_ERR_NULL: return "a required pointer is NULL";
+    case CHUNKKV_ERR_SHAPE: return "inconsistent shape, stride, alignment, budget or capacity";
+    case CHUNKKV_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or window rows per kv-head";
+    case CHUNKKV_ERR_WORKSPACE: return "workspace too small or NULL";
+    case CHUNKKV_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t chunkkv_workspace_bytes(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse) {
+  if (check_problem(prob, false) != CHUNKKV_OK) return 0;
+  Plan pl;
+  if (make_plan(prob, n_layers, reuse, &pl) != CHUNKKV_OK) return 0;
+  return pl.total;
+}
+
+int chunkkv_score(const chunkkv_problem *prob, const void *q_obs, const void *k, float *chunk_scores,
+                  float *token_importance, void *workspace, size_t workspace_bytes, void *stream) {
+  int rc = check_problem(prob, false);
+  if (rc) return rc;
+  if (!q_obs || !k || !chunk_scores) return CHUNKKV_ERR_NULL;
+  if (misaligned(q_obs) || misaligned(k)) return CHUNKKV_ERR_SHAPE;
+  Plan pl;
+  rc = make_plan(prob, 1, 1, &pl);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
+  return run_score(prob, pl, &q_obs, &k, 1, 0, chunk_scores, token_importance,
+                   (int64_t)prob->score_cap * prob->chunk, (char *)workspace, (hipStream_t)stream);
+}
+
+int chunkkv_chunk_topk(const chunkkv_problem *prob, const float *chunk_scores, int32_t *sel_chunk,
+                       int32_t *sel_len, int32_t *sel_count, void *workspace, size_t workspace_bytes,
+                       void *stream) {
+  (void)workspace; (void)workspace_bytes;  // the selection kernel keeps its state in LDS
+  int rc = check_problem(prob, false);
+  if (rc) return rc;
+  if (!chunk_scores || !sel_chunk || !sel_len || !sel_count) return CHUNKKV_ERR_NULL;
+  return run_topk(prob, chunk_scores, 1, sel_chunk, sel_len, sel_count, nullptr, (hipStream_t)stream);
+}
+
+int chunkkv_compact(const chunkkv_problem *prob, const void *k, const void *v, const int32_t *sel_chunk,
+                    const int32_t *sel_len, const int32_t *sel_count, void *k_out, void *v_out, void *stream) {
+  int rc = check_problem(prob, true);
+  if (rc) return rc;
+  if (!k || !v || !sel_chunk || !sel_len || !sel_count || !k_out || !v_out) return CHUNKKV_ERR_NULL;
+  if (misaligned(k) || misaligned(v) || misaligned(k_out) || misaligned(v_out)) return CHUNKKV_ERR_SHAPE;
+  return run_compact(prob, 1, 1, &k, &v, &k_out, &v_out, sel_chunk, sel_len, sel_count, nullptr,
+                     (hipStream_t)stream);
+}
+
+int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,
+                           const void *const *k, const void *const *v, void *const *k_out, void *const *v_out,
+                           int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  int rc = check_problem(prob, true);
+  if (rc) return rc;
+  if (n_layers < 1 || reuse < 1) return CHUNKKV_ERR_SHAPE;
+  if (!q_obs || !k || !v || !k_out || !v_out || !sel_chunk || !sel_len || !sel_count) return CHUNKKV_ERR_NULL;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!k[l] || !v[l] || !k_out[l] || !v_out[l]) return CHUNKKV_ERR_NULL;
+    if (l % reuse == 0 && !q_obs[l]) return CHUNKKV_ERR_NULL;
+    if (misaligned(k[l]) || misaligned(v[l]) || misaligned(k_out[l]) || misaligned(v_out[l])) return CHUNKKV_ERR_SHAPE;
+    if (l % reuse == 0 && misaligned(q_obs[l])) return CHUNKKV_ERR_SHAPE;
+  }
+  Plan pl;
+  rc = make_plan(prob, n_layers, reuse, &pl);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
+  char *ws = (char *)workspace;
+  hipStream_t s = (hipStream_t)stream;
+  float *scores = (float *)(ws + pl.off_scores);
+  int32_t *sel_off = (int32_t *)(ws + pl.off_seloff);
+
+  // Algorithm 2: score and select on the leader layers (l % reuse == 0) ...
+  for (int g0 = 0; g0 < pl.n_leaders; g0 += kMaxLayersPerLaunch) {
+    const int ng = pl.n_leaders - g0 < kMaxLayersPerLaunch ? pl.n_leaders - g0 : kMaxLayersPerLaunch;
+    const void *qs[kMaxLayersPerLaunch], *ks[kMaxLayersPerLaunch];
+    for (int i = 0; i < ng; ++i) { qs[i] = q_obs[(g0 + i) * reuse]; ks[i] = k[(g0 + i) * reuse]; }
+    rc = run_score(prob, pl, qs, ks, ng, g0, scores, nullptr, 0, ws, s);
+    if (rc) return rc;
+  }
+  rc = run_topk(prob, scores, pl.n_leaders, sel_chunk, sel_len, sel_count, sel_off, s);
+  if (rc) return rc;
+  // ... and gather every layer with the selection of its group.
+  return run_compact(prob, n_layers, reuse, k, v, k_out, v_out, sel_chunk, sel_len, sel_count, sel_off, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+// Compaction (Algorithm 1: index_select of the kept chunks + concatenation of the window).
+//
+// Pure data movement, bound by HBM bandwidth: every kept row of K and V is read once and written
+// once.  A kept chunk is a run of `len` consecutive rows, so each wavefront copies one selection entry
+// (K and V together) as 16-byte segments; with the default [Hkv][L][d] layout both source and
+// destination of an entry are contiguous, 256-byte aligned runs.  The window is handled as extra
+// entries of up to `c` rows each.  Grid: x = group of kCompactEntries entries, y = (sequence, kv-head),
+// z = layer; all layers of the stack are one launch.
+#include "internal.h"
+
+namespace ckv {
+
+template <int NSEG>  // 16-byte segments per row
+__global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int bl = blockIdx.y / a.n_kv_heads, h = blockIdx.y % a.n_kv_heads;
+  const int layer = blockIdx.z;
+  const int L = pick(a.seq.seqlen, bl), n_keep = pick(a.seq.n_keep, bl);
+  const int w = a.window, c = a.chunk, P = L - w;
+  const int group = (a.layer0 + layer) / a.reuse;
+  const int64_t selrow = ((int64_t)group * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
+  const int32_t *sel_chunk = a.sel_chunk + selrow * a.sel_cap;
+  const int32_t *sel_len = a.sel_len + selrow * a.sel_cap;
+  int count = n_keep > 0 ? a.sel_count[selrow] : 0;
+  count = count < 0 ? 0 : (count > a.sel_cap ? a.sel_cap : count);
+  const int n_win = (w + c - 1) / c;
+  const int e0 = blockIdx.x * kCompactEntries;
+  if (e0 >= count + n_win) return;
+
+  // Token offset of each entry of this workgroup inside the output.  The stack call passes the
+  // offsets the selection kernel already produced; the stand-alone call sums the lengths here.
+  __shared__ int s_off[kCompactEntries];
+  __shared__ int s_red[kThreads / 64];
+  if (a.sel_off == nullptr) {
+    const int lim = e0 < count ? e0 : count;
+    int part = 0;
+    for (int i = threadIdx.x; i < lim; i += kThreads) part += sel_len[i];
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+    if (lane == 0) s_red[wave] = part;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int run = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+      for (int i = 0; i < kCompactEntries; ++i) {
+        s_off[i] = run;
+        const int e = e0 + i;
+        if (e < count) run += sel_len[e];
+      }
+    }
+    __syncthreads();
+  }
+
+  const int64_t esz = a.elem_bytes;
+  const int64_t in_head = (pick(a.seq.kv_base, bl) + (int64_t)h * a.kv_stride_head) * esz;
+  const int64_t out_head = (pick(a.seq.out_base, bl) + (int64_t)h * a.out_stride_head) * esz;
+  const char *kin = (const char *)pick(a.k, layer) + in_head;
+  const char *vin = (const char *)pick(a.v, layer) + in_head;
+  char *kout = (char *)pick(a.k_out, layer) + out_head;
+  char *vout = (char *)pick(a.v_out, layer) + out_head;
+  const int64_t in_tok = a.kv_stride_tok * esz, out_tok = a.out_stride_tok * esz;
+
+  for (int i = wave; i < kCompactEntries; i += kThreads / 64) {
+    const int e = e0 + i;
+    if (e >= count + n_win) break;
+    int src_row, dst_row, len;
+    if (e < count) {
+      const int ch = sel_chunk[e];
+      len = sel_len[e];
+      src_row = ch * c;
+      dst_row = a.sel_off ? a.sel_off[selrow * a.sel_cap + e] : s_off[i];
+      // a malformed selection is skipped, never followed out of bounds
+      if (ch < 0 || len < 1 || len > c || (int64_t)ch * c + len > P || dst_row < 0 || dst_row + len > n_keep)
+        continue;
+    } else {
+      const int wi = e - count;
+      src_row = P + wi * c;
+      len = w - wi * c < c ? w - wi * c : c;
+      dst_row = n_keep + wi * c;
+    }
+    const int half = len * NSEG, total = 2 * half;
+    // segment u of the entry: K rows first, then V rows; lanes past the end re-read the last
+    // segment and store nothing
+    auto src_of = [&](int u) -> const uint4 * {
+      u = u < total ? u : total - 1;
+      const int t = u >= half, uu = u - t * half;
+      return (const uint4 *)((t ? vin : kin) + (int64_t)(src_row + uu / NSEG) * in_tok + (uu % NSEG) * 16);
+    };
+    auto dst_of = [&](int u) -> uint4 * {
+      const int t = u >= half, uu = u - t * half;
+      return (uint4 *)((t ? vout : kout) + (int64_t)(dst_row + uu / NSEG) * out_tok + (uu % NSEG) * 16);
+    };
+    for (int base = lane; base < total; base += 64 * 4) {
+      const uint4 r0 = *src_of(base), r1 = *src_of(base + 64), r2 = *src_of(base + 128), r3 = *src_of(base + 192);
+      *dst_of(base) = r0;
+      if (base + 64 < total) *dst_of(base + 64) = r1;
+      if (base + 128 < total) *dst_of(base + 128) = r2;
+      if (base + 192 < total) *dst_of(base + 192) = r3;
+    }
+  }
+}
+
+int launch_compact(int row_bytes, const CompactArgs &a, int n_layers_slice, int batch_slice, int max_entries,
+                   hipStream_t s) {
+  if (n_layers_slice <= 0 || batch_slice <= 0 || max_entries <= 0) return CHUNKKV_OK;
+  dim3 grid((max_entries + kCompactEntries - 1) / kCompactEntries, batch_slice * a.n_kv_heads, n_layers_slice);
+  switch (row_bytes / 16) {
+    case 8: hipLaunchKernelGGL(compact_kernel<8>, grid, dim3(kThreads), 0, s, a); break;
+    case 16: hipLaunchKernelGGL(compact_kernel<16>, grid, dim3(kThreads), 0, s, a); break;
+    case 32: hipLaunchKernelGGL(compact_kernel<32>, grid, dim3(kThreads), 0, s, a); break;
+    default: return CHUNKKV_ERR_UNSUPPORTED;
+  }
+  return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
+}
+
+}  // namespace ckv

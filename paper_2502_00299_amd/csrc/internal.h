@@ -1,0 +1,103 @@
+// Internal declarations shared by the translation units of libchunkkv (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "chunkkv.h"
+
+namespace ckv {
+
+constexpr int kMaxLayersPerLaunch = 32;  // pointer tables travel as kernel arguments
+constexpr int kMaxBatchPerLaunch = 16;
+constexpr int kTileBytes = 32768;        // one K tile staged in LDS
+constexpr int kThreads = 256;            // 4 wavefronts of 64
+constexpr int kMaxRows = 512;            // g * w limit
+constexpr int kCompactEntries = 16;      // selection entries per compaction workgroup
+
+// Per-sequence metadata of one launch slice (<= kMaxBatchPerLaunch sequences).
+struct SeqTable {
+  int32_t seqlen[kMaxBatchPerLaunch];
+  int32_t n_keep[kMaxBatchPerLaunch];
+  int64_t kv_base[kMaxBatchPerLaunch];
+  int64_t out_base[kMaxBatchPerLaunch];
+};
+
+// Arguments of the two scoring passes.  "problem" = (leader layer, sequence, kv-head).
+// Arrays indexed by problem use the FULL batch (batch_total) so slices address the same buffers.
+struct ScoreArgs {
+  const void *q[kMaxLayersPerLaunch];
+  const void *k[kMaxLayersPerLaunch];
+  SeqTable seq;
+  int32_t leader0;         // index of this slice's first leader layer
+  int32_t batch0;          // index of this slice's first sequence
+  int32_t batch_total;
+  int32_t n_q_heads, n_kv_heads, window, chunk;
+  int64_t kv_stride_head, kv_stride_tok;
+  float scale_log2e;       // softmax scale * log2(e)
+  int32_t tiles_per_wg;    // key tiles each workgroup walks
+  int32_t max_split;       // pitch of part_stats in splits
+  int32_t rows_pad;        // g*w rounded up to 32
+  float2 *part_stats;      // [problem][max_split][rows_pad]  (running max, sum) in log2 units
+  float *refs;             // [problem][rows_pad]  max + log2(sum)
+  float *chunk_scores;     // [leader][batch_total][Hkv][score_cap]
+  int32_t score_cap;
+  float *token_imp;        // [leader][batch_total][Hkv][imp_pitch] or null
+  int64_t imp_pitch;
+  int32_t fuse_chunks;     // pass 1: 1 = tiles hold whole chunks and chunk sums are written
+};
+
+struct TopkArgs {
+  SeqTable seq;
+  int32_t batch0, batch_total, n_kv_heads, window, chunk;
+  const float *chunk_scores;  // [group][batch_total][Hkv][score_cap]
+  int32_t score_cap, sel_cap;
+  int32_t *sel_chunk, *sel_len, *sel_count;
+  int32_t *sel_off;           // [group][batch_total][Hkv][sel_cap] exclusive token offsets, or null
+};
+
+struct CompactArgs {
+  const void *k[kMaxLayersPerLaunch];
+  const void *v[kMaxLayersPerLaunch];
+  void *k_out[kMaxLayersPerLaunch];
+  void *v_out[kMaxLayersPerLaunch];
+  SeqTable seq;
+  int32_t layer0, reuse;      // selection group of slice layer z is (layer0 + z) / reuse
+  int32_t batch0, batch_total, n_kv_heads, window, chunk;
+  int32_t elem_bytes;
+  int64_t kv_stride_head, kv_stride_tok, out_stride_head, out_stride_tok;
+  const int32_t *sel_chunk, *sel_len, *sel_count, *sel_off;  // sel_off may be null
+  int32_t sel_cap;
+};
+
+// Reads element i of a small table that travels as a kernel argument.  A chain of selects on the
+// (wavefront-uniform) index keeps the table in scalar registers; a dynamic subscript would make the
+// compiler copy the whole argument struct to scratch memory first.
+template <typename T, int N>
+__device__ __forceinline__ T pick(const T (&arr)[N], int i) {
+  T r = arr[0];
+#pragma unroll
+  for (int j = 1; j < N; ++j) r = (i == j) ? arr[j] : r;
+  return r;
+}
+
+// Geometry of the scoring kernels for one (dtype, head_dim, row count).
+struct ScoreGeom {
+  int row_bytes;   // head_dim * sizeof(element)
+  int tile_keys;   // keys per LDS tile
+  int nq_blocks;   // 32-row blocks of window rows (padded)
+  int nqw;         // blocks held by one wavefront
+  int wq;          // wavefronts splitting the rows (the other 4/wq split keys)
+};
+bool score_geometry(int dtype, int head_dim, int rows, ScoreGeom *g);
+
+// Launchers (each checks hipGetLastError and returns a chunkkv_status).
+int launch_score_pass(int pass, int dtype, int head_dim, const ScoreGeom &g, const ScoreArgs &a,
+                      dim3 grid, hipStream_t s);
+int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slice, int tile_keys,
+                         hipStream_t s);
+int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
+int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s);
+int launch_compact(int row_bytes, const CompactArgs &a, int n_layers_slice, int batch_slice,
+                   int max_entries, hipStream_t s);
+
+}  // namespace ckv

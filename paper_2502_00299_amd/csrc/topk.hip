@@ -1,0 +1,170 @@
+// Chunk selection (Algorithm 1, top-k step, with the exact-budget rule).
+//
+// One workgroup per (selection group, sequence, kv-head).  Chunks are ranked by (score descending,
+// index ascending).  The m highest-ranked chunks are found with a most-significant-digit radix select
+// over the order-preserving integer image of the fp32 scores (4 passes of 8 bits, histograms in LDS);
+// ties at the threshold value are resolved towards the lower index by a prefix count in index order.
+// m = ceil(n_keep / c); if the ragged last chunk is among those m and leaves the budget short, one
+// more chunk is taken.  The lowest-ranked selected chunk is cut to the tokens still missing.
+// Entries are emitted in ascending chunk order with a block-wide prefix scan; their exclusive token
+// offsets are written next to them for the compaction kernel.
+#include "internal.h"
+
+namespace ckv {
+
+constexpr int kTopkThreads = 1024;
+
+__device__ __forceinline__ uint32_t order_key(float x) {
+  uint32_t u = __float_as_uint(x);
+  if (u == 0x80000000u) u = 0;  // -0 ranks as +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Block-wide exclusive scan of one int per thread (1024 threads); returns the exclusive prefix and
+// stores the block total in *total.  s_tmp needs 16 ints.  Ends with a barrier.
+__device__ __forceinline__ int block_exscan(int x, int *s_tmp, int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = x;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(inc, o);
+    if (lane >= o) inc += y;
+  }
+  __syncthreads();
+  if (lane == 63) s_tmp[wave] = inc;
+  __syncthreads();
+  int wave_base = 0, tot = 0;
+  for (int i = 0; i < kTopkThreads / 64; ++i) {
+    const int v = s_tmp[i];
+    if (i < wave) wave_base += v;
+    tot += v;
+  }
+  *total = tot;
+  return wave_base + inc - x;
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
+  const int tid = threadIdx.x;
+  const int bl = blockIdx.x / a.n_kv_heads, h = blockIdx.x % a.n_kv_heads, group = blockIdx.y;
+  const int64_t row = ((int64_t)group * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
+  const float *scores = a.chunk_scores + row * a.score_cap;
+  int32_t *sel_chunk = a.sel_chunk + row * a.sel_cap;
+  int32_t *sel_len = a.sel_len + row * a.sel_cap;
+  int32_t *sel_off = a.sel_off ? a.sel_off + row * a.sel_cap : nullptr;
+  const int c = a.chunk, P = pick(a.seq.seqlen, bl) - a.window, n_keep = pick(a.seq.n_keep, bl);
+  const int C = (P + c - 1) / c;
+  if (n_keep <= 0 || C <= 0) {
+    if (tid == 0) a.sel_count[row] = 0;
+    return;
+  }
+  const int tail_size = P - (C - 1) * c;  // == c when there is no ragged tail
+  const int m0 = (n_keep + c - 1) / c;
+
+  __shared__ int s_hist[256];
+  __shared__ int s_tmp[16];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_remaining;
+  __shared__ int s_pos_trunc;
+
+  uint32_t thr = 0;   // key of the lowest-ranked selected chunk
+  int need = 0;       // how many chunks with key == thr are selected (lowest indices first)
+  int m = m0, total = 0;
+  bool tail_sel = false;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    // ---- radix select: the m-th largest key
+    if (tid == 0) { s_prefix = 0; s_remaining = m; }
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < 256) s_hist[tid] = 0;
+      __syncthreads();
+      const uint32_t prefix = s_prefix;
+      const uint32_t mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+      for (int i = tid; i < C; i += kTopkThreads) {
+        const uint32_t key = order_key(scores[i]);
+        if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (tid < 64) {
+        // lane l owns digits 255-4l .. 252-4l (descending); find where the running count reaches `remaining`
+        const int rem = s_remaining;
+        int v[4], sum = 0;
+        for (int j = 0; j < 4; ++j) { v[j] = s_hist[255 - 4 * tid - j]; sum += v[j]; }
+        int inc = sum;
+        for (int o = 1; o < 64; o <<= 1) {
+          const int y = __shfl_up(inc, o);
+          if (tid >= o) inc += y;
+        }
+        int before = inc - sum;  // keys with a larger digit than this lane's first
+        if (before < rem && inc >= rem) {
+          for (int j = 0; j < 4; ++j) {
+            if (before + v[j] >= rem) {
+              s_prefix = prefix | ((uint32_t)(255 - 4 * tid - j) << shift);
+              s_remaining = rem - before;
+              break;
+            }
+            before += v[j];
+          }
+        }
+      }
+      __syncthreads();
+    }
+    thr = s_prefix;
+    need = s_remaining;  // rank of the threshold chunk among the chunks with key == thr, 1-based
+    // ---- does the ragged tail chunk belong to the m selected?  It has the highest index, so among
+    // equal keys it is taken last: selected iff key > thr, or key == thr and every equal key is taken.
+    if (tid < 256) s_hist[tid] = 0;
+    __syncthreads();
+    int eq = 0;
+    for (int i = tid; i < C; i += kTopkThreads) eq += order_key(scores[i]) == thr;
+    if (eq) atomicAdd(&s_hist[0], eq);
+    __syncthreads();
+    const int cnt_eq = s_hist[0];
+    const uint32_t tail_key = order_key(scores[C - 1]);
+    tail_sel = tail_key > thr || (tail_key == thr && need == cnt_eq);
+    total = m * c - (tail_sel ? c - tail_size : 0);
+    __syncthreads();
+    if (total >= n_keep) break;
+    m = m0 + 1;  // tail selected and budget short by < c tokens: exactly one more chunk is needed
+  }
+  // The lowest-ranked selected chunk is the need-th (index order) chunk with key == thr.  It is the
+  // tail iff the tail's key == thr and the tail is selected.
+  const bool trunc_is_tail = tail_sel && order_key(scores[C - 1]) == thr;
+  const int size_trunc = trunc_is_tail ? tail_size : c;
+  const int len_trunc = n_keep - (total - size_trunc);
+
+  // ---- emit in ascending chunk order
+  if (tid == 0) s_pos_trunc = 0x7FFFFFFF;
+  int base_sel = 0, base_eq = 0;
+  for (int i0 = 0; i0 < C; i0 += kTopkThreads) {
+    const int i = i0 + tid;
+    uint32_t key = 0;
+    if (i < C) key = order_key(scores[i]);
+    const int is_eq = i < C && key == thr;
+    int tot_eq, tot_sel;
+    const int eq_rank = base_eq + block_exscan(is_eq, s_tmp, &tot_eq);
+    const int flag = i < C && (key > thr || (is_eq && eq_rank < need));
+    const int pos = base_sel + block_exscan(flag, s_tmp, &tot_sel);
+    if (flag && pos < a.sel_cap) {
+      const bool is_trunc = is_eq && eq_rank == need - 1;
+      sel_chunk[pos] = i;
+      sel_len[pos] = is_trunc ? len_trunc : (i == C - 1 ? tail_size : c);
+      if (is_trunc) s_pos_trunc = pos;
+    }
+    base_eq += tot_eq;
+    base_sel += tot_sel;
+    __syncthreads();
+  }
+  if (sel_off) {
+    const int pos_trunc = s_pos_trunc;
+    for (int p = tid; p < m && p < a.sel_cap; p += kTopkThreads)
+      sel_off[p] = p * c - (p > pos_trunc ? size_trunc - len_trunc : 0);
+  }
+  if (tid == 0) a.sel_count[row] = m;
+}
+
+int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s) {
+  if (n_groups <= 0 || batch_slice <= 0) return CHUNKKV_OK;
+  dim3 grid(batch_slice * a.n_kv_heads, n_groups);
+  hipLaunchKernelGGL(topk_kernel, grid, dim3(kTopkThreads), 0, s, a);
+  return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
+}
+
+}  // namespace ckv

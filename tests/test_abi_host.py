@@ -1,0 +1,121 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, and every argument check returns its status before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2502_00299_amd as pkg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pkg.LIB_PATH):
+        from paper_2502_00299_amd import build
+        build.build(verbose=False)
+    return pkg.load_library()
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "chunkkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(chunkkv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = header_functions()
+    assert set(names) == set(pkg.SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = {lib.chunkkv_status_string(i).decode() for i in range(6)}
+    assert len(seen) == 6 and "ok" in seen
+    assert lib.chunkkv_status_string(99).decode() == "unknown status"
+
+
+def good(**kw):
+    d = dict(n_q_heads=32, n_kv_heads=8, head_dim=128, window=32, chunk=10, dtype=pkg.BF16, seqlen=[8192],
+             n_keep=[816], kv_base=[0], kv_stride_head=8192 * 128, kv_stride_tok=128)
+    d.update(kw)
+    return pkg.Problem(**d)
+
+
+FAKE = C.c_void_p(0x1000)  # never dereferenced: every call below fails its argument check first
+
+
+def score_rc(lib, prob, q=FAKE, k=FAKE, out=FAKE, ws=FAKE, ws_bytes=1 << 40):
+    return lib.chunkkv_score(C.byref(prob.as_c()), q, k, out, None, ws, ws_bytes, None)
+
+
+def test_workspace_size_is_positive_and_grows_with_layers(lib):
+    p = good()
+    a = pkg.chunkkv_workspace_bytes(p, 1, 1)
+    b = pkg.chunkkv_workspace_bytes(p, 32, 1)
+    c = pkg.chunkkv_workspace_bytes(p, 32, 2)
+    assert 0 < a < c < b
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_q_heads=30), 2),                       # Hq % Hkv != 0
+    (dict(window=0), 2),
+    (dict(chunk=0), 2),
+    (dict(seqlen=[16]), 2),                        # w > L
+    (dict(n_keep=[8161]), 2),                      # n_keep > P
+    (dict(n_keep=[-1]), 2),
+    (dict(sel_cap=5), 2),                          # needs ceil(816/10)+1 = 83
+    (dict(score_cap=10), 2),                       # needs 816
+    (dict(kv_stride_tok=100), 2),                  # < head_dim
+    (dict(kv_stride_tok=132), 2),                  # rows not 16-byte aligned
+    (dict(kv_base=[3]), 2),
+    (dict(softmax_scale=-1.0), 2),
+    (dict(head_dim=96), 3),
+    (dict(dtype=7), 3),
+    (dict(window=64, n_q_heads=128, n_keep=[100]), 3),   # g*w = 1024 rows > 512
+])
+def test_problem_validation(lib, kw, status):
+    p = good(**kw)
+    assert score_rc(lib, p) == status
+    assert pkg.chunkkv_workspace_bytes(p) == 0
+
+
+def test_null_pointers_and_workspace(lib):
+    p = good()
+    assert lib.chunkkv_score(None, FAKE, FAKE, FAKE, None, FAKE, 1 << 40, None) == 1
+    assert score_rc(lib, p, q=None) == 1
+    assert score_rc(lib, p, k=None) == 1
+    assert score_rc(lib, p, out=None) == 1
+    assert score_rc(lib, p, q=C.c_void_p(0x1004)) == 2             # misaligned device pointer
+    assert score_rc(lib, p, ws=None) == 4
+    assert score_rc(lib, p, ws_bytes=pkg.chunkkv_workspace_bytes(p) - 1) == 4
+    cp = p.as_c()
+    assert lib.chunkkv_chunk_topk(C.byref(cp), None, FAKE, FAKE, FAKE, None, 0, None) == 1
+    assert lib.chunkkv_compact(C.byref(cp), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, None) == 1
+    bad_out = good(out_base=[0], out_stride_head=848 * 128, out_stride_tok=100)
+    assert lib.chunkkv_compact(C.byref(bad_out.as_c()), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == 2
+
+
+def test_stack_argument_checks(lib):
+    p = good()
+    cp = p.as_c()
+    n = 4
+    tab = (C.c_void_p * n)(*[0x1000] * n)
+    hole = (C.c_void_p * n)(0x1000, None, 0x1000, None)
+    ws = pkg.chunkkv_workspace_bytes(p, n, 2)
+    call = lambda q, k, reuse, nl=n, wsb=ws: lib.chunkkv_compress_stack(
+        C.byref(cp), nl, reuse, q, k, tab, tab, tab, FAKE, FAKE, FAKE, FAKE, wsb, None)
+    assert call(tab, tab, 0) == 2                  # R < 1
+    assert call(tab, tab, 2, nl=0) == 2
+    assert call(hole, hole, 2) == 1                # K of layer 1 missing
+    assert call(hole, tab, 1) == 1                 # every layer needs Q when R = 1
+    assert call(tab, tab, 2, wsb=ws - 1) == 4
+    assert call(None, tab, 2) == 1
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        pkg.load_library(str(tmp_path / "nope.so"))

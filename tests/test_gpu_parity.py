@@ -1,0 +1,258 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Bars: chunk scores / token importance within 1e-3 relative; selections bit-exact on hand-made
+scores (ties included) and, when the scores come from the GPU, equal up to chunks inside the
+1e-3 tie band around the threshold (count printed); gathered K/V bit-exact for the given indices."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import chunkkv_oracle as orc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def small(name, **kw):
+    return W.get_workload(name).with_(**kw)
+
+
+def alloc_sel(prob, groups=1):
+    B, Hk = prob.batch, prob.n_kv_heads
+    return (torch.full((groups, B, Hk, prob.sel_cap), -7, dtype=torch.int32, device=DEV),
+            torch.full((groups, B, Hk, prob.sel_cap), -7, dtype=torch.int32, device=DEV),
+            torch.full((groups, B, Hk), -7, dtype=torch.int32, device=DEV))
+
+
+def workspace(lib, prob, n_layers=1, reuse=1):
+    n = lib.chunkkv_workspace_bytes(prob, n_layers, reuse)
+    assert n > 0
+    return torch.empty(n, dtype=torch.uint8, device=DEV)
+
+
+# ------------------------------------------------------------------ scoring
+SCORE_CASES = {
+    # name: workload (sizes span several 64..256-key tiles, ragged tails, every row-block geometry)
+    "tiny_f32": small("tiny"),
+    "f32_d128": small("tiny", head_dim=128, seqlens=(300,), window=8, chunk=7),
+    "f32_rows160": small("tiny", n_q_heads=10, n_kv_heads=2, window=32, seqlens=(333,), chunk=5),
+    "bf16_8k": small("llama8b_8k"),
+    "bf16_rows32": small("llama8b_8k", n_q_heads=2, n_kv_heads=2, window=32, seqlens=(1000,), n_spans=(5,)),
+    "bf16_rows64_d64": small("llama8b_8k", n_q_heads=4, n_kv_heads=2, head_dim=64, window=32, seqlens=(1531,),
+                             chunk=3, n_spans=(5,)),
+    "bf16_rows96": small("llama8b_8k", n_q_heads=6, n_kv_heads=2, window=16, seqlens=(777,), chunk=20, n_spans=(5,)),
+    "bf16_rows224_g7": small("ragged_b8", seqlens=(2049, 517), n_spans=(10, 2), n_layers=1),
+    "bf16_rows256_w64": small("llama8b_128k_stack", seqlens=(4100,), n_spans=(20,), n_layers=1),
+    "bf16_rows512": small("llama8b_8k", n_q_heads=16, n_kv_heads=2, window=64, seqlens=(700,), n_spans=(4,)),
+    "bf16_chunk1": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(515,), chunk=1, n_spans=(4,)),
+    "bf16_chunk_gt_tile": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(1200,), chunk=300, n_spans=(4,)),
+    "bf16_P0": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(32,), n_spans=(0,)),
+    "bf16_P_lt_chunk": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(37,), n_spans=(0,)),
+}
+
+
+@pytest.mark.parametrize("case", list(SCORE_CASES))
+def test_score_matches_oracle(lib, case):
+    wl = SCORE_CASES[case]
+    li = W.make_layer(wl, 0, DEV)
+    prob = H.make_problem(lib, wl, li)
+    B, Hk = wl.batch, wl.n_kv_heads
+    cs = torch.full((B, Hk, prob.score_cap), -1.0, dtype=torch.float32, device=DEV)
+    imp = torch.full((B, Hk, prob.score_cap * wl.chunk), -1.0, dtype=torch.float32, device=DEV)
+    ws = workspace(lib, prob)
+    print(f"case={case} L={wl.seqlens} rows={wl.group * wl.window}", flush=True)
+    lib.chunkkv_score(prob, li.q, li.k, cs, imp, ws)
+    torch.cuda.synchronize()
+    cs_h, imp_h = cs.cpu().numpy(), imp.cpu().numpy()
+    worst = 0.0
+    for b in range(B):
+        q, k, _ = H.seq_arrays(wl, li, b)
+        P = wl.seqlens[b] - wl.window
+        o_cs, o_imp = orc.score(q, k, wl.window, wl.chunk)
+        C = orc.n_chunks(P, wl.chunk)
+        for h in range(Hk):
+            worst = max(worst, H.rel_err(imp_h[b, h, :P], o_imp[h]), H.rel_err(cs_h[b, h, :C], o_cs[h]))
+            assert np.all(cs_h[b, h, C:] == -1.0) and np.all(imp_h[b, h, P:] == -1.0)  # nothing written past the end
+    print(f"max relative error {worst:.3e}")
+    assert worst <= H.REL_TOL
+    # without the optional importance output the chunk scores are identical
+    cs2 = torch.zeros_like(cs)
+    lib.chunkkv_score(prob, li.q, li.k, cs2, None, ws)
+    torch.cuda.synchronize()
+    for b in range(B):
+        C = orc.n_chunks(wl.seqlens[b] - wl.window, wl.chunk)
+        assert torch.equal(cs2[b, :, :C], cs[b, :, :C])
+
+
+def test_score_custom_scale_and_determinism(lib):
+    wl = small("llama8b_8k", seqlens=(2000,), n_spans=(8,))
+    li = W.make_layer(wl, 0, DEV)
+    prob = H.make_problem(lib, wl, li, softmax_scale=0.05)
+    cs = torch.zeros((1, 8, prob.score_cap), dtype=torch.float32, device=DEV)
+    ws = workspace(lib, prob)
+    lib.chunkkv_score(prob, li.q, li.k, cs, None, ws)
+    first = cs.clone()
+    lib.chunkkv_score(prob, li.q, li.k, cs, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, cs)                       # fixed-order reductions: bit-identical reruns
+    q, k, _ = H.seq_arrays(wl, li, 0)
+    o_cs, _ = orc.score(q, k, wl.window, wl.chunk, scale=0.05)
+    assert H.rel_err(cs.cpu().numpy()[0], o_cs) <= H.REL_TOL
+
+
+# ------------------------------------------------------------------ selection
+def topk_case(lib, P, c, n_keep_list, scores_rows):
+    """scores_rows: [B][Hkv][C] float32.  Compares with the oracle bit-exactly."""
+    B, Hk = len(n_keep_list), len(scores_rows[0])
+    w = 4
+    prob = lib.Problem(Hk, Hk, 64, w, c, lib.F32, [P + w] * B, n_keep_list, [0] * B, (P + w) * 64, 64)
+    C = orc.n_chunks(P, c)
+    sc = torch.zeros((B, Hk, prob.score_cap), dtype=torch.float32, device=DEV)
+    if C:
+        sc[:, :, :C] = torch.tensor(np.asarray(scores_rows, dtype=np.float32), device=DEV)
+    sel_chunk, sel_len, sel_count = alloc_sel(prob)
+    lib.chunkkv_chunk_topk(prob, sc, sel_chunk, sel_len, sel_count)
+    torch.cuda.synchronize()
+    got = H.read_selection(prob, sel_chunk, sel_len, sel_count)
+    for b in range(B):
+        for h in range(Hk):
+            oc, ol = orc.chunk_topk(np.asarray(scores_rows[b][h], dtype=np.float32).astype(np.float64), P, c, n_keep_list[b])
+            gc, gl = got[b][h]
+            assert np.array_equal(gc, oc) and np.array_equal(gl, ol), (P, c, n_keep_list[b], b, h)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_random_with_ties_bit_exact(lib, seed):
+    r = np.random.default_rng(500 + seed)
+    P = int(r.integers(1, 5000))
+    c = int(r.choice([1, 2, 3, 5, 8, 10, 20, 33]))
+    C = orc.n_chunks(P, c)
+    B, Hk = 3, 4
+    levels = int(r.choice([2, 5, 50, 100000]))
+    rows = (r.integers(0, levels, size=(B, Hk, C)) / levels).astype(np.float32)
+    if seed % 2:
+        rows[:, :, -1] = 1.5          # the ragged tail ranks first
+    n_keep = [int(r.integers(0, P + 1)) for _ in range(B)]
+    print(f"P={P} c={c} levels={levels} n_keep={n_keep}", flush=True)
+    topk_case(lib, P, c, n_keep, rows)
+
+
+def test_topk_edge_cases(lib):
+    topk_case(lib, 23, 10, [13, 10, 14, 0, 23, 1], [[[0.1, 0.5, 0.9]]] * 6)      # ragged tail spill-over
+    topk_case(lib, 43, 10, [25, 43, 7], [[[0.5] * 5]] * 3)                         # all equal: leading tokens
+    topk_case(lib, 7, 10, [0, 3, 7], [[[0.25]]] * 3)                               # one ragged chunk (c > P)
+    topk_case(lib, 40, 1, [0, 17, 40], [[list(np.linspace(0, 1, 40) % 0.3)]] * 3)  # token-level
+    topk_case(lib, 3000, 10, [300], [[list(np.zeros(300))]])                       # all-zero scores
+    big = np.random.default_rng(3).random(13101).astype(np.float32)                # 128K-token chunk count
+    topk_case(lib, 131008, 10, [13100, 26201], [[big]] * 2)
+
+
+def test_topk_negative_zero_and_tiny_values(lib):
+    rows = np.array([[[0.0, -0.0, 1e-38, 0.0, 1e-45, -0.0, 3.0, 0.0]]], dtype=np.float32)
+    for nk in range(0, 17):
+        topk_case(lib, 16, 2, [nk], rows)
+
+
+# ------------------------------------------------------------------ gather
+def random_selection(r, P, c, n_keep):
+    """A valid selection that keeps exactly n_keep tokens (not necessarily what top-k would give)."""
+    C = orc.n_chunks(P, c)
+    return orc.chunk_topk(r.random(C), P, c, n_keep)
+
+
+@pytest.mark.parametrize("case", ["tiny_f32", "bf16_8k", "bf16_rows224_g7", "bf16_rows64_d64", "f32_d128",
+                                  "bf16_chunk1", "bf16_P0", "bf16_P_lt_chunk"])
+def test_compact_bit_exact(lib, case):
+    wl = SCORE_CASES[case]
+    li = W.make_layer(wl, 0, DEV)
+    r = np.random.default_rng(11)
+    B, Hk = wl.batch, wl.n_kv_heads
+    for variant in ("budget", "all", "none"):
+        n_keep = [{"budget": W.keep_budget(L, wl.window, wl.keep_pct), "all": L - wl.window, "none": 0}[variant]
+                  for L in wl.seqlens]
+        prob = H.make_problem(lib, wl, li, n_keep=n_keep)
+        sel_chunk, sel_len, sel_count = alloc_sel(prob)
+        sels = [[random_selection(r, L - wl.window, wl.chunk, n_keep[b]) for _ in range(Hk)]
+                for b, L in enumerate(wl.seqlens)]
+        for b in range(B):
+            for h in range(Hk):
+                ch, ln = sels[b][h]
+                sel_chunk[0, b, h, :len(ch)] = torch.from_numpy(ch).to(DEV)
+                sel_len[0, b, h, :len(ln)] = torch.from_numpy(ln).to(DEV)
+                sel_count[0, b, h] = len(ch)
+        k_out = torch.zeros(prob.out_elements(), dtype=li.k.dtype, device=DEV)
+        v_out = torch.zeros_like(k_out)
+        print(f"case={case} variant={variant} n_keep={n_keep}", flush=True)
+        lib.chunkkv_compact(prob, li.k, li.v, sel_chunk, sel_len, sel_count, k_out, v_out)
+        torch.cuda.synchronize()
+        for b in range(B):
+            _, k, v = H.seq_arrays(wl, li, b)
+            ok, ov = orc.compact(k, v, [s[0] for s in sels[b]], [s[1] for s in sels[b]], wl.window, wl.chunk)
+            assert np.array_equal(W.tensor_bits(H.out_view(prob, k_out, b)), ok)
+            assert np.array_equal(W.tensor_bits(H.out_view(prob, v_out, b)), ov)
+        if variant == "all" and wl.layout == "hnd":
+            assert torch.equal(k_out.view_as(li.k), li.k) and torch.equal(v_out.view_as(li.v), li.v)
+
+
+# ------------------------------------------------------------------ whole stack
+STACK_CASES = {
+    "tiny_f32_x3": (small("tiny", n_layers=3), [1, 2, 3]),
+    "bf16_4k_x5": (small("llama8b_32k_stack", seqlens=(4096,), n_spans=(20,), n_layers=5), [1, 2, 4, 7]),
+    "ragged_x4": (small("ragged_b8", seqlens=(1500, 640, 2304), n_spans=(7, 3, 11), n_layers=4, chunk=5, keep_pct=30), [1, 3]),
+    "w64_20pct_x2": (small("llama8b_128k_stack", seqlens=(3000,), n_spans=(9,), n_layers=2, keep_pct=20), [2]),
+}
+
+
+@pytest.mark.parametrize("case", list(STACK_CASES))
+def test_compress_stack_matches_oracle(lib, case):
+    wl, reuses = STACK_CASES[case]
+    N, B, Hk = wl.n_layers, wl.batch, wl.n_kv_heads
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    # oracle scores and selections of every layer (each may be a leader for some R)
+    o_scores = [[orc.score(*H.seq_arrays(wl, layers[l], b)[:2], wl.window, wl.chunk)[0] for b in range(B)]
+                for l in range(N)]
+    for R in reuses:
+        G = (N + R - 1) // R
+        sel_chunk, sel_len, sel_count = alloc_sel(prob, G)
+        k_out = [torch.zeros(prob.out_elements(), dtype=layers[0].k.dtype, device=DEV) for _ in range(N)]
+        v_out = [torch.zeros_like(k_out[0]) for _ in range(N)]
+        ws = workspace(lib, prob, N, R)
+        q_list = [layers[l].q if l % R == 0 else None for l in range(N)]
+        print(f"case={case} R={R}", flush=True)
+        lib.chunkkv_compress_stack(prob, R, q_list, [x.k for x in layers], [x.v for x in layers], k_out, v_out,
+                                   sel_chunk, sel_len, sel_count, ws)
+        torch.cuda.synchronize()
+        n_diff = 0
+        for grp in range(G):
+            leader = grp * R
+            got = H.read_selection(prob, sel_chunk, sel_len, sel_count, grp)
+            for b in range(B):
+                P, nk = wl.seqlens[b] - wl.window, int(prob.n_keep[b])
+                for h in range(Hk):
+                    o_sel = orc.chunk_topk(o_scores[leader][b][h], P, wl.chunk, nk)
+                    n_diff += H.check_selection(got[b][h], o_sel, o_scores[leader][b][h], P, wl.chunk, nk)
+            # gather of every layer of the group, bit-exact for the selection the GPU produced
+            for l in range(leader, min(leader + R, N)):
+                for b in range(B):
+                    _, k, v = H.seq_arrays(wl, layers[l], b)
+                    ok, ov = orc.compact(k, v, [s[0] for s in got[b]], [s[1] for s in got[b]], wl.window, wl.chunk)
+                    assert np.array_equal(W.tensor_bits(H.out_view(prob, k_out[l], b)), ok), (l, b)
+                    assert np.array_equal(W.tensor_bits(H.out_view(prob, v_out[l], b)), ov), (l, b)
+        print(f"R={R}: chunks differing inside the tie band: {n_diff}")
+
+
+def test_stack_keep_everything_is_identity(lib):
+    wl = small("llama8b_8k", seqlens=(1111,), n_spans=(3,), n_layers=3, keep_pct=100)
+    layers = [W.make_layer(wl, l, DEV) for l in range(3)]
+    prob = H.make_problem(lib, wl, layers[0])
+    sel_chunk, sel_len, sel_count = alloc_sel(prob, 2)
+    k_out = [torch.zeros_like(x.k) for x in layers]
+    v_out = [torch.zeros_like(x.v) for x in layers]
+    lib.chunkkv_compress_stack(prob, 2, [layers[0].q, None, layers[2].q], [x.k for x in layers], [x.v for x in layers],
+                               k_out, v_out, sel_chunk, sel_len, sel_count, workspace(lib, prob, 3, 2))
+    torch.cuda.synchronize()
+    for l in range(3):
+        assert torch.equal(k_out[l], layers[l].k) and torch.equal(v_out[l], layers[l].v)
