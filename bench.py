@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the ChunkKV compression stack on one MI355X.
+
+A step is one chunkkv_compress_stack call over the whole synthetic cache (all layers: scoring and
+selection on the leader layers, gather on every layer), inputs resident in HBM.  The metric is prefix
+tokens compressed per second over the layer stack.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as W  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(wl, n_keep, n_layers, reuse):
+    """Bytes the method must move: K read once per scored layer; kept K and V rows read once and
+    written once on every layer.  Q_obs, chunk scores and selections are < 0.3 % and left out."""
+    row = wl.head_dim * wl.elem_bytes
+    k_read = sum(wl.n_kv_heads * L * row for L in wl.seqlens)
+    gather = sum(4 * wl.n_kv_heads * (nk + wl.window) * row for nk in n_keep)
+    leaders = (n_layers + reuse - 1) // reuse
+    return {"score_per_layer": k_read, "gather_per_layer": gather,
+            "stack": leaders * k_read + n_layers * gather}
+
+
+def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers):
+    """The oracle, as it stands, on the first n_sample_layers layers of the same inputs."""
+    from oracle import chunkkv_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    host = []
+    for l in range(n_sample_layers):
+        li = layers[l]
+        per_seq = []
+        for b in range(wl.batch):
+            q = W.tensor_bits(li.q[b]) if l % reuse == 0 else None
+            k = W.tensor_bits(li.seq_view(li.k, b, wl.n_kv_heads, wl.head_dim))
+            v = W.tensor_bits(li.seq_view(li.v, b, wl.n_kv_heads, wl.head_dim))
+            per_seq.append((q, k, v))
+        host.append(per_seq)
+    t0 = time.perf_counter()
+    for b in range(wl.batch):
+        orc.compress_stack([host[l][b][0] for l in range(n_sample_layers)],
+                           [host[l][b][1] for l in range(n_sample_layers)],
+                           [host[l][b][2] for l in range(n_sample_layers)],
+                           wl.window, wl.chunk, n_keep[b], reuse)
+    dt = time.perf_counter() - t0
+    est_stack = dt * wl.n_layers / n_sample_layers
+    return {"value": sum(wl.seqlens) / est_stack, "unit": "prefix tokens/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": f"layers 0..{n_sample_layers - 1} of {wl.n_layers} (all sequences and kv-heads) in "
+                      f"{dt:.1f} s, scaled by {wl.n_layers}/{n_sample_layers}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b_128k_stack")
+    ap.add_argument("--reuse", type=int, default=2)
+    ap.add_argument("--keep-pct", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-layers", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+
+    import paper_2502_00299_amd as ckv
+    ckv.load_library()
+    dev = "cuda:0"
+    wl = W.get_workload(args.workload)
+    if args.keep_pct is not None:
+        wl = wl.with_(keep_pct=args.keep_pct)
+    if args.layers is not None:
+        wl = wl.with_(n_layers=args.layers)
+    N, R = wl.n_layers, args.reuse
+    log(f"generating {wl.name}: {N} layers, L={wl.seqlens}, w={wl.window}, c={wl.chunk}, keep {wl.keep_pct}%")
+    layers = [W.make_layer(wl, l, dev) for l in range(N)]
+    torch.cuda.synchronize()
+    n_keep = [W.keep_budget(L, wl.window, wl.keep_pct) for L in wl.seqlens]
+    li0 = layers[0]
+    prob = ckv.Problem(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                       ckv.F32 if wl.dtype == "f32" else ckv.BF16, list(wl.seqlens), n_keep, list(li0.kv_base),
+                       li0.kv_stride_head, li0.kv_stride_tok)
+    k_out = [torch.empty(prob.out_elements(), dtype=wl.torch_dtype, device=dev) for _ in range(N)]
+    v_out = [torch.empty(prob.out_elements(), dtype=wl.torch_dtype, device=dev) for _ in range(N)]
+    ks, vs = [x.k for x in layers], [x.v for x in layers]
+
+    def make_run(reuse):
+        G = (N + reuse - 1) // reuse
+        sel_chunk = torch.zeros((G, wl.batch, wl.n_kv_heads, prob.sel_cap), dtype=torch.int32, device=dev)
+        sel_len = torch.zeros_like(sel_chunk)
+        sel_count = torch.zeros((G, wl.batch, wl.n_kv_heads), dtype=torch.int32, device=dev)
+        ws = torch.empty(ckv.chunkkv_workspace_bytes(prob, N, reuse), dtype=torch.uint8, device=dev)
+        qs = [layers[l].q if l % reuse == 0 else None for l in range(N)]
+
+        def run():
+            ckv.chunkkv_compress_stack(prob, reuse, qs, ks, vs, k_out, v_out, sel_chunk, sel_len, sel_count, ws)
+        return run
+
+    def timed(run, steps, warmup, with_kernel_timing=False):
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        if with_kernel_timing:
+            ckv.chunkkv_timing_begin(16 * steps + 16)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        kt = ckv.chunkkv_timing_end() if with_kernel_timing else None
+        return dt / steps * 1e3, kt
+
+    ms, kt = timed(make_run(R), args.steps, args.warmup, with_kernel_timing=True)
+    tokens = sum(wl.seqlens)
+    value = tokens / (ms * 1e-3)
+    ab = algorithmic_bytes(wl, n_keep, N, R)
+    leaders = (N + R - 1) // R
+
+    # roofline of the kernel that takes the most time (durations from HIP events on the launch stream)
+    kern = {k: {"ms_per_launch": t / n, "launches_per_step": n / args.steps, "ms_per_step": t / args.steps}
+            for k, (t, n) in kt.items() if n}
+    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    launches = kern[dom]["launches_per_step"]
+    if dom in ("score_stats", "score_colsum"):
+        bytes_per_launch = ab["score_per_layer"] * leaders / launches
+    elif dom == "compact":
+        bytes_per_launch = ab["gather_per_layer"] * N / launches
+    else:
+        bytes_per_launch = 0.0
+    achieved = bytes_per_launch / (kern[dom]["ms_per_launch"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                "algorithmic_bytes_per_launch": bytes_per_launch}
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            roofline["traffic"] = json.load(open(traffic_file)).get(wl.name, {}).get(dom)
+        except Exception:
+            pass
+    stack_gbps = ab["stack"] / (ms * 1e-3) / 1e9
+
+    # index reuse: same stack with R = 1
+    ms_r1 = None
+    if R != 1:
+        ms_r1, _ = timed(make_run(1), max(3, args.steps // 2), 2)
+
+    out = {
+        "metric": "prefix tokens compressed/sec (32-layer stack) + achieved HBM GB/s vs peak",
+        "value": value, "unit": "prefix tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {N} layers, B={wl.batch}, L={list(wl.seqlens)}, Hq={wl.n_q_heads}, "
+                               f"Hkv={wl.n_kv_heads}, d={wl.head_dim}, w={wl.window}, c={wl.chunk}, "
+                               f"keep {wl.keep_pct}%, R={R}",
+                   "reuse": R, "n_layers": N, "keep_pct": wl.keep_pct},
+        "roofline": roofline,
+        "stack_hbm": {"algorithmic_bytes": ab["stack"], "achieved": stack_gbps, "peak": HBM_PEAK_GBPS,
+                      "unit": "GB/s", "frac": stack_gbps / HBM_PEAK_GBPS},
+        "kernels_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in kern.items()},
+        "reuse_speedup_vs_R1": (ms_r1 / ms) if ms_r1 else None,
+        "ms_per_step_R1": ms_r1,
+    }
+    if not args.no_cpu:
+        n_cpu = args.cpu_layers or min(N, 2 * R if wl.seqlens[0] > 65536 else 4 * R)
+        log(f"timing the CPU oracle on {n_cpu} layers ...")
+        out["cpu_baseline"] = cpu_baseline(wl, layers, n_keep, R, n_cpu)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

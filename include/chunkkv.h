@@ -112,6 +112,18 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
                            void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
                            int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Measurement aid (the per-kernel durations the roofline figures need; Algorithm 2's T_compress and
+ * T_select are the scoring+selection and the gather durations).  Between begin and end every kernel
+ * the calls above launch is bracketed by a HIP event pair on its stream (up to max_records launches).
+ * chunkkv_timing_end waits for those events and returns, per kernel kind, the summed duration in
+ * milliseconds and the number of launches:
+ *   0 score pass 0 (softmax statistics)   1 statistics merge   2 score pass 1 (importance, chunk sums)
+ *   3 chunk sums for c larger than a key tile   4 chunk selection   5 compaction
+ * total_ms and launches are host arrays of CHUNKKV_TIMING_KINDS entries.  Not thread-safe.          */
+#define CHUNKKV_TIMING_KINDS 6
+int chunkkv_timing_begin(int32_t max_records);
+int chunkkv_timing_end(double *total_ms, int64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,6 +15,9 @@ from .binding import (  # noqa: F401
     chunkkv_compress_stack,
     chunkkv_score,
     chunkkv_status_string,
+    chunkkv_timing_begin,
+    chunkkv_timing_end,
+    TIMING_KINDS,
     chunkkv_workspace_bytes,
     load_library,
 )

@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_PKG, "libchunkkv.so")
 
 F32, BF16 = 0, 1
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
-           "chunkkv_compact", "chunkkv_compress_stack")
+           "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_timing_begin", "chunkkv_timing_end")
+TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact")
 
 
 class ChunkKVError(RuntimeError):
@@ -199,3 +200,21 @@ def chunkkv_compress_stack(prob: Problem, reuse: int, q_obs: Sequence, k: Sequen
         _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
         "chunkkv_compress_stack")
+
+
+def chunkkv_timing_begin(max_records: int = 4096) -> None:
+    lib = load_library()
+    lib.chunkkv_timing_begin.restype = C.c_int
+    lib.chunkkv_timing_begin.argtypes = [C.c_int32]
+    _check(lib.chunkkv_timing_begin(max_records), "chunkkv_timing_begin")
+
+
+def chunkkv_timing_end() -> dict:
+    """-> {kind: (total milliseconds, launches)} for the kernels launched since chunkkv_timing_begin."""
+    lib = load_library()
+    n = len(TIMING_KINDS)
+    ms, cnt = (C.c_double * n)(), (C.c_int64 * n)()
+    lib.chunkkv_timing_end.restype = C.c_int
+    lib.chunkkv_timing_end.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    _check(lib.chunkkv_timing_end(ms, cnt), "chunkkv_timing_end")
+    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(TIMING_KINDS)}

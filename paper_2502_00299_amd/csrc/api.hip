@@ -17,6 +17,30 @@ struct Plan {
   size_t off_part, off_refs, off_scores, off_seloff, off_imp, total;
 };
 
+// ---- optional per-kernel timing (chunkkv_timing_begin / chunkkv_timing_end) -----------------------
+enum Kind { kStats = 0, kCombine, kColsum, kChunkSums, kTopk, kCompact, kKinds };
+struct Timing {
+  bool on = false;
+  int cap = 0, used = 0;
+  hipEvent_t *ev = nullptr;  // 2 per record
+  int *kind = nullptr;
+} g_timing;
+
+struct Timed {  // records an event pair around one launch when timing is on
+  hipStream_t s;
+  int slot = -1;
+  Timed(int kind, hipStream_t stream) : s(stream) {
+    if (g_timing.on && g_timing.used < g_timing.cap) {
+      slot = g_timing.used++;
+      g_timing.kind[slot] = kind;
+      (void)hipEventRecord(g_timing.ev[2 * slot], s);
+    }
+  }
+  ~Timed() {
+    if (slot >= 0) (void)hipEventRecord(g_timing.ev[2 * slot + 1], s);
+  }
+};
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -133,15 +157,15 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
     }
     int rc;
     a.tiles_per_wg = pl.tpw0;
-    rc = launch_score_pass(0, p->dtype, p->head_dim, pl.geom, a, dim3(split0, nb * p->n_kv_heads, ng), s);
+    { Timed t(kStats, s); rc = launch_score_pass(0, p->dtype, p->head_dim, pl.geom, a, dim3(split0, nb * p->n_kv_heads, ng), s); }
     if (rc) return rc;
-    rc = launch_stats_combine(a, ng, nb, TK, s);
+    { Timed t(kCombine, s); rc = launch_stats_combine(a, ng, nb, TK, s); }
     if (rc) return rc;
     a.tiles_per_wg = pl.tpw1;
-    rc = launch_score_pass(1, p->dtype, p->head_dim, pl.geom, a, dim3(split1, nb * p->n_kv_heads, ng), s);
+    { Timed t(kColsum, s); rc = launch_score_pass(1, p->dtype, p->head_dim, pl.geom, a, dim3(split1, nb * p->n_kv_heads, ng), s); }
     if (rc) return rc;
     if (!pl.fuse_chunks) {
-      rc = launch_chunk_sums(a, ng, nb, s);
+      { Timed t(kChunkSums, s); rc = launch_chunk_sums(a, ng, nb, s); }
       if (rc) return rc;
     }
   }
@@ -158,7 +182,8 @@ int run_topk(const chunkkv_problem *p, const float *chunk_scores, int n_groups, 
     a.batch0 = b0; a.batch_total = p->batch; a.n_kv_heads = p->n_kv_heads; a.window = p->window; a.chunk = p->chunk;
     a.chunk_scores = chunk_scores; a.score_cap = p->score_cap; a.sel_cap = p->sel_cap;
     a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
-    const int rc = launch_topk(a, n_groups, nb, s);
+    int rc;
+    { Timed t(kTopk, s); rc = launch_topk(a, n_groups, nb, s); }
     if (rc) return rc;
   }
   return CHUNKKV_OK;
@@ -191,7 +216,8 @@ int run_compact(const chunkkv_problem *p, int n_layers, int reuse, const void *c
         if (nk > 0 && e - ceil_div(p->window, p->chunk) > p->sel_cap) e = p->sel_cap + ceil_div(p->window, p->chunk);
         max_entries = e > max_entries ? e : max_entries;
       }
-      const int rc = launch_compact(p->head_dim * esz, a, nl, nb, max_entries, s);
+      int rc;
+      { Timed t(kCompact, s); rc = launch_compact(p->head_dim * esz, a, nl, nb, max_entries, s); }
       if (rc) return rc;
     }
   }
@@ -293,6 +319,41 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
   if (rc) return rc;
   // ... and gather every layer with the selection of its group.
   return run_compact(prob, n_layers, reuse, k, v, k_out, v_out, sel_chunk, sel_len, sel_count, sel_off, s);
+}
+
+int chunkkv_timing_begin(int32_t max_records) {
+  if (g_timing.on || max_records < 1) return CHUNKKV_ERR_SHAPE;
+  g_timing.ev = new hipEvent_t[2 * (size_t)max_records];
+  g_timing.kind = new int[max_records];
+  for (int i = 0; i < 2 * max_records; ++i)
+    if (hipEventCreate(&g_timing.ev[i]) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+  g_timing.cap = max_records;
+  g_timing.used = 0;
+  g_timing.on = true;
+  return CHUNKKV_OK;
+}
+
+int chunkkv_timing_end(double *total_ms, int64_t *launches) {
+  if (!g_timing.on) return CHUNKKV_ERR_SHAPE;
+  if (!total_ms || !launches) return CHUNKKV_ERR_NULL;
+  g_timing.on = false;
+  for (int k = 0; k < kKinds; ++k) { total_ms[k] = 0; launches[k] = 0; }
+  int rc = CHUNKKV_OK;
+  for (int i = 0; i < g_timing.used; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_timing.ev[2 * i + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_timing.ev[2 * i], g_timing.ev[2 * i + 1]) != hipSuccess) {
+      rc = CHUNKKV_ERR_LAUNCH;
+      continue;
+    }
+    total_ms[g_timing.kind[i]] += ms;
+    launches[g_timing.kind[i]] += 1;
+  }
+  for (int i = 0; i < 2 * g_timing.cap; ++i) (void)hipEventDestroy(g_timing.ev[i]);
+  delete[] g_timing.ev;
+  delete[] g_timing.kind;
+  g_timing.ev = nullptr; g_timing.kind = nullptr; g_timing.cap = g_timing.used = 0;
+  return rc;
 }
 
 }  // extern "C"
