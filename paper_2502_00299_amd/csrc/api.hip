@@ -86,8 +86,8 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   pl->n_leaders = ceil_div(n_layers, reuse);
   pl->rows_pad = pl->geom.nqw * pl->geom.wq * 32;
   const int TK = pl->geom.tile_keys;
-  pl->fuse_chunks = p->chunk <= TK;
-  const int stride1 = pl->fuse_chunks ? (TK / p->chunk) * p->chunk : TK;
+  pl->fuse_chunks = p->chunk <= kSuperKeys;
+  const int stride1 = pl->fuse_chunks ? (kSuperKeys / p->chunk) * p->chunk : kSuperKeys;
   int64_t tiles0 = 0, tiles1 = 0;
   for (int b = 0; b < p->batch; ++b) {
     tiles0 += ceil_div(p->seqlen[b], TK);
@@ -148,7 +148,7 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
     a.fuse_chunks = pl.fuse_chunks;
     if (!pl.fuse_chunks && !token_imp) { a.token_imp = (float *)(ws + pl.off_imp); a.imp_pitch = (int64_t)p->score_cap * p->chunk; }
     int split0 = 1, split1 = 0;
-    const int stride1 = pl.fuse_chunks ? (TK / p->chunk) * p->chunk : TK;
+    const int stride1 = pl.fuse_chunks ? (kSuperKeys / p->chunk) * p->chunk : kSuperKeys;
     for (int i = 0; i < nb; ++i) {
       const int s0 = ceil_div(ceil_div(a.seq.seqlen[i], TK), pl.tpw0);
       const int s1 = ceil_div(ceil_div(a.seq.seqlen[i] - p->window, stride1), pl.tpw1);

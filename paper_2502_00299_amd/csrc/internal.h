@@ -9,7 +9,8 @@ namespace ckv {
 
 constexpr int kMaxLayersPerLaunch = 32;  // pointer tables travel as kernel arguments
 constexpr int kMaxBatchPerLaunch = 16;
-constexpr int kTileBytes = 32768;        // one K tile staged in LDS
+constexpr int kTileBytes = 16384;        // one K tile staged in LDS (ring slot)
+constexpr int kSuperKeys = 256;        // keys per importance / chunk-sum step of pass 1 (several tiles)
 constexpr int kThreads = 256;            // 4 wavefronts of 64
 constexpr int kMaxRows = 512;            // g * w limit
 constexpr int kCompactEntries = 16;      // selection entries per compaction workgroup
@@ -34,7 +35,7 @@ struct ScoreArgs {
   int32_t n_q_heads, n_kv_heads, window, chunk;
   int64_t kv_stride_head, kv_stride_tok;
   float scale_log2e;       // softmax scale * log2(e)
-  int32_t tiles_per_wg;    // key tiles each workgroup walks
+  int32_t tiles_per_wg;    // pass 0: key tiles, pass 1: super-tiles (kSuperKeys) each workgroup walks
   int32_t max_split;       // pitch of part_stats in splits
   int32_t rows_pad;        // g*w rounded up to 32
   float2 *part_stats;      // [problem][max_split][rows_pad]  (running max, sum) in log2 units
@@ -43,7 +44,7 @@ struct ScoreArgs {
   int32_t score_cap;
   float *token_imp;        // [leader][batch_total][Hkv][imp_pitch] or null
   int64_t imp_pitch;
-  int32_t fuse_chunks;     // pass 1: 1 = tiles hold whole chunks and chunk sums are written
+  int32_t fuse_chunks;     // pass 1: 1 = super-tiles hold whole chunks and chunk sums are written
 };
 
 struct TopkArgs {
