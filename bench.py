@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-layers", type=int, default=None)
+    ap.add_argument("--no-r1", action="store_true", help="skip the R=1 comparison run")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
@@ -138,7 +139,11 @@ def main():
         kt = ckv.chunkkv_timing_end() if with_kernel_timing else None
         return dt / steps * 1e3, kt
 
-    ms, kt = timed(make_run(R), args.steps, args.warmup, with_kernel_timing=True)
+    run_main = make_run(R)
+    ms, _ = timed(run_main, args.steps, args.warmup)
+    # per-kernel durations: a second loop of the same steps with a HIP event pair around every launch
+    # (kept out of the headline loop: the event packets add gaps between the kernels)
+    _, kt = timed(run_main, args.steps, 1, with_kernel_timing=True)
     tokens = sum(wl.seqlens)
     value = tokens / (ms * 1e-3)
     ab = algorithmic_bytes(wl, n_keep, N, R)
@@ -169,7 +174,7 @@ def main():
 
     # index reuse: same stack with R = 1
     ms_r1 = None
-    if R != 1:
+    if R != 1 and not args.no_r1:
         ms_r1, _ = timed(make_run(1), max(3, args.steps // 2), 2)
 
     out = {

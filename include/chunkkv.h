@@ -112,6 +112,14 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
                            void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
                            int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream);
 
+/* chunkkv_compress_stack scores the leader layers in sets and gathers each set's layers right after its
+ * selection.  With chunkkv_set_overlap(1) the gather of a set is enqueued on an internal helper stream
+ * (created on first use, default priority, ordered after `stream`'s prior work and joined back into it
+ * with events before the call returns) so that it can run beside the scoring of the next set.  The
+ * default is 0: everything on `stream` (on MI355X the scoring kernels leave no register room for
+ * co-resident gather wavefronts, so the helper stream does not pay off yet).                        */
+int chunkkv_set_overlap(int32_t enable);
+
 /* Measurement aid (the per-kernel durations the roofline figures need; Algorithm 2's T_compress and
  * T_select are the scoring+selection and the gather durations).  Between begin and end every kernel
  * the calls above launch is bracketed by a HIP event pair on its stream (up to max_records launches).

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     chunkkv_compact,
     chunkkv_compress_stack,
     chunkkv_score,
+    chunkkv_set_overlap,
     chunkkv_status_string,
     chunkkv_timing_begin,
     chunkkv_timing_end,

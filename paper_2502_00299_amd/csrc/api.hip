@@ -8,10 +8,14 @@ namespace ckv {
 namespace {
 
 constexpr int kTargetWorkgroups = 2048;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
+// Key tiles (16 KB) one scoring launch set should hold.  Measured on MI355X: every extra dependent launch
+// costs ~30 us of idle GPU, more than splitting the stack into sets wins back, so one set it is.
+constexpr int64_t kTilesPerLaunch = 1 << 30;
 
 struct Plan {
   ScoreGeom geom;
   int n_leaders, rows_pad;
+  int batch_leaders;  // leader layers scored per launch set (the unit that overlaps with compaction)
   int tpw0, tpw1, max_split0;
   int fuse_chunks;
   size_t off_part, off_refs, off_scores, off_seloff, off_imp, total;
@@ -41,6 +45,27 @@ struct Timed {  // records an event pair around one launch when timing is on
   }
 };
 
+// ---- helper stream for overlapping the gather with scoring inside chunkkv_compress_stack ----------
+bool g_overlap_enabled = false;
+struct Overlap {
+  hipStream_t side = nullptr;
+  static constexpr int kEvents = 128;
+  hipEvent_t ev[kEvents];
+  int cur = -1;
+  hipEvent_t next_event() { cur = (cur + 1) % kEvents; return ev[cur]; }
+  hipEvent_t last_event() const { return ev[cur]; }
+};
+Overlap *overlap_state() {  // created on first use; default priority; lives until the process ends
+  static Overlap *st = [] {
+    Overlap *o = new Overlap;
+    if (hipStreamCreateWithFlags(&o->side, hipStreamNonBlocking) != hipSuccess) { delete o; return (Overlap *)nullptr; }
+    for (int i = 0; i < Overlap::kEvents; ++i)
+      if (hipEventCreateWithFlags(&o->ev[i], hipEventDisableTiming) != hipSuccess) { delete o; return (Overlap *)nullptr; }
+    return o;
+  }();
+  return st;
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -60,6 +85,7 @@ int check_problem(const chunkkv_problem *p, bool need_out) {
   const int esz = p->dtype == CHUNKKV_BF16 ? 2 : 4;
   if (p->kv_stride_tok < p->head_dim || p->kv_stride_head < 0) return CHUNKKV_ERR_SHAPE;
   if ((p->kv_stride_tok * esz) % 16 || (p->kv_stride_head * esz) % 16) return CHUNKKV_ERR_SHAPE;
+  if (p->kv_stride_tok * esz > (1 << 22)) return CHUNKKV_ERR_UNSUPPORTED;  // tile offsets are 32-bit
   if (need_out) {
     if (p->out_stride_tok < p->head_dim || p->out_stride_head < 0) return CHUNKKV_ERR_SHAPE;
     if ((p->out_stride_tok * esz) % 16 || (p->out_stride_head * esz) % 16) return CHUNKKV_ERR_SHAPE;
@@ -93,7 +119,16 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
     tiles0 += ceil_div(p->seqlen[b], TK);
     tiles1 += ceil_div(p->seqlen[b] - p->window, stride1);
   }
-  const int64_t heads = (int64_t)pl->n_leaders * p->n_kv_heads;
+  // leader layers per launch set: enough key tiles (~kTilesPerLaunch) to amortise workgroup start-up,
+  // few enough that compaction of one set overlaps scoring of the next; sets are balanced in size
+  int64_t per_leader = tiles0 * p->n_kv_heads;
+  int gb = (int)((kTilesPerLaunch + per_leader - 1) / (per_leader > 0 ? per_leader : 1));
+  if (gb < 1) gb = 1;
+  if (gb > pl->n_leaders) gb = pl->n_leaders;
+  if (gb > kMaxLayersPerLaunch) gb = kMaxLayersPerLaunch;
+  const int nsets = ceil_div(pl->n_leaders, gb);
+  pl->batch_leaders = ceil_div(pl->n_leaders, nsets);
+  const int64_t heads = (int64_t)pl->batch_leaders * p->n_kv_heads;
   pl->tpw0 = (int)((tiles0 * heads + kTargetWorkgroups - 1) / kTargetWorkgroups);
   pl->tpw1 = (int)((tiles1 * heads + kTargetWorkgroups - 1) / kTargetWorkgroups);
   if (pl->tpw0 < 1) pl->tpw0 = 1;
@@ -172,13 +207,14 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
   return CHUNKKV_OK;
 }
 
-int run_topk(const chunkkv_problem *p, const float *chunk_scores, int n_groups, int32_t *sel_chunk,
+int run_topk(const chunkkv_problem *p, const float *chunk_scores, int group0, int n_groups, int32_t *sel_chunk,
              int32_t *sel_len, int32_t *sel_count, int32_t *sel_off, hipStream_t s) {
   for (int b0 = 0; b0 < p->batch; b0 += kMaxBatchPerLaunch) {
     const int nb = p->batch - b0 < kMaxBatchPerLaunch ? p->batch - b0 : kMaxBatchPerLaunch;
     TopkArgs a;
     memset(&a, 0, sizeof(a));
     fill_seq(&a.seq, p, b0, nb);
+    a.group0 = group0;
     a.batch0 = b0; a.batch_total = p->batch; a.n_kv_heads = p->n_kv_heads; a.window = p->window; a.chunk = p->chunk;
     a.chunk_scores = chunk_scores; a.score_cap = p->score_cap; a.sel_cap = p->sel_cap;
     a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
@@ -189,11 +225,11 @@ int run_topk(const chunkkv_problem *p, const float *chunk_scores, int n_groups, 
   return CHUNKKV_OK;
 }
 
-int run_compact(const chunkkv_problem *p, int n_layers, int reuse, const void *const *k, const void *const *v,
+int run_compact(const chunkkv_problem *p, int l_begin, int n_layers, int reuse, const void *const *k, const void *const *v,
                 void *const *k_out, void *const *v_out, const int32_t *sel_chunk, const int32_t *sel_len,
                 const int32_t *sel_count, const int32_t *sel_off, hipStream_t s) {
   const int esz = p->dtype == CHUNKKV_BF16 ? 2 : 4;
-  for (int l0 = 0; l0 < n_layers; l0 += kMaxLayersPerLaunch) {
+  for (int l0 = l_begin; l0 < n_layers; l0 += kMaxLayersPerLaunch) {
     const int nl = n_layers - l0 < kMaxLayersPerLaunch ? n_layers - l0 : kMaxLayersPerLaunch;
     for (int b0 = 0; b0 < p->batch; b0 += kMaxBatchPerLaunch) {
       const int nb = p->batch - b0 < kMaxBatchPerLaunch ? p->batch - b0 : kMaxBatchPerLaunch;
@@ -271,7 +307,7 @@ int chunkkv_chunk_topk(const chunkkv_problem *prob, const float *chunk_scores, i
   int rc = check_problem(prob, false);
   if (rc) return rc;
   if (!chunk_scores || !sel_chunk || !sel_len || !sel_count) return CHUNKKV_ERR_NULL;
-  return run_topk(prob, chunk_scores, 1, sel_chunk, sel_len, sel_count, nullptr, (hipStream_t)stream);
+  return run_topk(prob, chunk_scores, 0, 1, sel_chunk, sel_len, sel_count, nullptr, (hipStream_t)stream);
 }
 
 int chunkkv_compact(const chunkkv_problem *prob, const void *k, const void *v, const int32_t *sel_chunk,
@@ -280,7 +316,7 @@ int chunkkv_compact(const chunkkv_problem *prob, const void *k, const void *v, c
   if (rc) return rc;
   if (!k || !v || !sel_chunk || !sel_len || !sel_count || !k_out || !v_out) return CHUNKKV_ERR_NULL;
   if (misaligned(k) || misaligned(v) || misaligned(k_out) || misaligned(v_out)) return CHUNKKV_ERR_SHAPE;
-  return run_compact(prob, 1, 1, &k, &v, &k_out, &v_out, sel_chunk, sel_len, sel_count, nullptr,
+  return run_compact(prob, 0, 1, 1, &k, &v, &k_out, &v_out, sel_chunk, sel_len, sel_count, nullptr,
                      (hipStream_t)stream);
 }
 
@@ -307,18 +343,43 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
   float *scores = (float *)(ws + pl.off_scores);
   int32_t *sel_off = (int32_t *)(ws + pl.off_seloff);
 
-  // Algorithm 2: score and select on the leader layers (l % reuse == 0) ...
-  for (int g0 = 0; g0 < pl.n_leaders; g0 += kMaxLayersPerLaunch) {
-    const int ng = pl.n_leaders - g0 < kMaxLayersPerLaunch ? pl.n_leaders - g0 : kMaxLayersPerLaunch;
+  // Algorithm 2: leader layers (l % reuse == 0) are scored and selected set by set on `stream`; the
+  // gather of a set's layers (pure HBM traffic) runs on the helper stream while the next set is
+  // scored (matrix/vector bound), and is joined back into `stream` before the call returns.
+  Overlap *ov = g_overlap_enabled ? overlap_state() : nullptr;
+  if (ov && hipEventRecord(ov->next_event(), s) == hipSuccess) {
+    (void)hipStreamWaitEvent(ov->side, ov->last_event(), 0);  // helper stream starts after the caller's prior work
+  } else {
+    ov = nullptr;
+  }
+  for (int g0 = 0; g0 < pl.n_leaders; g0 += pl.batch_leaders) {
+    const int ng = pl.n_leaders - g0 < pl.batch_leaders ? pl.n_leaders - g0 : pl.batch_leaders;
     const void *qs[kMaxLayersPerLaunch], *ks[kMaxLayersPerLaunch];
     for (int i = 0; i < ng; ++i) { qs[i] = q_obs[(g0 + i) * reuse]; ks[i] = k[(g0 + i) * reuse]; }
     rc = run_score(prob, pl, qs, ks, ng, g0, scores, nullptr, 0, ws, s);
     if (rc) return rc;
+    rc = run_topk(prob, scores, g0, ng, sel_chunk, sel_len, sel_count, sel_off, s);
+    if (rc) return rc;
+    const int l_begin = g0 * reuse, l_end = (g0 + ng) * reuse < n_layers ? (g0 + ng) * reuse : n_layers;
+    hipStream_t cs = s;
+    if (ov) {
+      if (hipEventRecord(ov->next_event(), s) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+      if (hipStreamWaitEvent(ov->side, ov->last_event(), 0) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+      cs = ov->side;
+    }
+    rc = run_compact(prob, l_begin, l_end, reuse, k, v, k_out, v_out, sel_chunk, sel_len, sel_count, sel_off, cs);
+    if (rc) return rc;
   }
-  rc = run_topk(prob, scores, pl.n_leaders, sel_chunk, sel_len, sel_count, sel_off, s);
-  if (rc) return rc;
-  // ... and gather every layer with the selection of its group.
-  return run_compact(prob, n_layers, reuse, k, v, k_out, v_out, sel_chunk, sel_len, sel_count, sel_off, s);
+  if (ov) {
+    if (hipEventRecord(ov->next_event(), ov->side) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+    if (hipStreamWaitEvent(s, ov->last_event(), 0) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+  }
+  return CHUNKKV_OK;
+}
+
+int chunkkv_set_overlap(int32_t enable) {
+  g_overlap_enabled = enable != 0;
+  return CHUNKKV_OK;
 }
 
 int chunkkv_timing_begin(int32_t max_records) {

@@ -49,6 +49,7 @@ struct ScoreArgs {
 
 struct TopkArgs {
   SeqTable seq;
+  int32_t group0;             // first selection group of this launch
   int32_t batch0, batch_total, n_kv_heads, window, chunk;
   const float *chunk_scores;  // [group][batch_total][Hkv][score_cap]
   int32_t score_cap, sel_cap;

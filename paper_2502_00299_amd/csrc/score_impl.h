@@ -121,18 +121,35 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
   // Tile i -> ring slot i % kRing.  Lane l of a 1 KB group lands at byte 16*l of the group, i.e. at
   // (key, segment position l % NSEG); it fetches segment (position ^ key&7) of that key.  Keys past
   // the sequence are clamped to the last row (never read out of bounds; their results are masked).
+  // The lane's byte offset inside a tile is the same for every tile (scalar tile base + 32-bit lane
+  // offset, no per-tile vector address arithmetic); only tiles reaching past L take the clamped path.
+  uint32_t lane_off[kLoadsPerWave];
+#pragma unroll
+  for (int j = 0; j < kLoadsPerWave; ++j) {
+    const int key = (wave * kLoadsPerWave + j) * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
+    lane_off[j] = (uint32_t)(key * (int)ktok + ((segp ^ (key & 7)) * 16));
+  }
   auto issue_tile = [&](int i) {
     const int fk0 = tile_key0(i);
     char *slot = smem + (i % kRing) * kTileBytes;
+    if (fk0 + TK <= L) {
+      const char *tbase = kbase + (int64_t)fk0 * ktok;  // wavefront-uniform
 #pragma unroll
-    for (int j = 0; j < kLoadsPerWave; ++j) {
-      const int grp = wave * kLoadsPerWave + j;
-      const int key = grp * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
-      int gk = fk0 + key;
-      gk = gk < L ? gk : L - 1;
-      const char *src = kbase + (int64_t)gk * ktok + ((segp ^ (key & 7)) * 16);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                       (__attribute__((address_space(3))) void *)(slot + grp * 1024), 16, 0, 0);
+      for (int j = 0; j < kLoadsPerWave; ++j)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(tbase + lane_off[j]),
+                                         (__attribute__((address_space(3))) void *)(slot + (wave * kLoadsPerWave + j) * 1024),
+                                         16, 0, 0);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kLoadsPerWave; ++j) {
+        const int grp = wave * kLoadsPerWave + j;
+        const int key = grp * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
+        int gk = fk0 + key;
+        gk = gk < L ? gk : L - 1;
+        const char *src = kbase + (int64_t)gk * ktok + ((segp ^ (key & 7)) * 16);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                         (__attribute__((address_space(3))) void *)(slot + grp * 1024), 16, 0, 0);
+      }
     }
   };
   // tile i has landed once at most min(2, tiles issued after it) newer tile loads are outstanding

@@ -44,7 +44,7 @@ __device__ __forceinline__ int block_exscan(int x, int *s_tmp, int *total) {
 
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
   const int tid = threadIdx.x;
-  const int bl = blockIdx.x / a.n_kv_heads, h = blockIdx.x % a.n_kv_heads, group = blockIdx.y;
+  const int bl = blockIdx.x / a.n_kv_heads, h = blockIdx.x % a.n_kv_heads, group = a.group0 + blockIdx.y;
   const int64_t row = ((int64_t)group * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
   const float *scores = a.chunk_scores + row * a.score_cap;
   int32_t *sel_chunk = a.sel_chunk + row * a.sel_cap;
