@@ -1,0 +1,161 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(one chunkkv_compress_stack call over the whole stack).
+
+The oracle cannot redo a 32-layer 128K cache in seconds, so:
+  * selections are compared with the oracle on sampled (group, sequence, kv-head) problems (tie-band rule);
+  * structural properties are checked for EVERY (group, sequence, kv-head): exact budget, ascending
+    chunks, valid lengths, at most one cut chunk;
+  * the gather is checked for EVERY layer and head against torch.index_select with the indices
+    the GPU's own selection names (a library gather, independent of the HIP kernels), bit-exact;
+  * chunk scores of sampled heads are compared with the oracle at full length (chunkkv_score).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import chunkkv_oracle as orc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def run_stack(lib, wl, R, layers=None):
+    N, B, Hk = wl.n_layers, wl.batch, wl.n_kv_heads
+    layers = layers or [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    G = (N + R - 1) // R
+    sel_chunk = torch.zeros((G, B, Hk, prob.sel_cap), dtype=torch.int32, device=DEV)
+    sel_len = torch.zeros_like(sel_chunk)
+    sel_count = torch.zeros((G, B, Hk), dtype=torch.int32, device=DEV)
+    k_out = [torch.zeros(prob.out_elements(), dtype=wl.torch_dtype, device=DEV) for _ in range(N)]
+    v_out = [torch.zeros(prob.out_elements(), dtype=wl.torch_dtype, device=DEV) for _ in range(N)]
+    ws = torch.empty(lib.chunkkv_workspace_bytes(prob, N, R), dtype=torch.uint8, device=DEV)
+    qs = [layers[l].q if l % R == 0 else None for l in range(N)]
+    lib.chunkkv_compress_stack(prob, R, qs, [x.k for x in layers], [x.v for x in layers], k_out, v_out,
+                               sel_chunk, sel_len, sel_count, ws)
+    torch.cuda.synchronize()
+    return layers, prob, (sel_chunk, sel_len, sel_count), k_out, v_out
+
+
+def check_structure_everywhere(wl, prob, sel, R):
+    sel_chunk, sel_len, sel_count = (t.cpu().numpy() for t in sel)
+    G = sel_chunk.shape[0]
+    c = wl.chunk
+    for g in range(G):
+        for b in range(wl.batch):
+            P, nk = wl.seqlens[b] - wl.window, int(prob.n_keep[b])
+            for h in range(wl.n_kv_heads):
+                m = int(sel_count[g, b, h])
+                ch, ln = sel_chunk[g, b, h, :m].astype(np.int64), sel_len[g, b, h, :m].astype(np.int64)
+                assert int(ln.sum()) == nk
+                assert np.all(np.diff(ch) > 0) and (m == 0 or (ch[0] >= 0 and ch[-1] * c < P))
+                natural = np.minimum(c, P - ch * c)
+                assert np.all((ln >= 1) & (ln <= natural)) and int(np.sum(ln < natural)) <= 1
+
+
+def check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, R):
+    """Every layer and head: output == index_select(input, tokens named by the GPU selection)."""
+    sel_chunk, sel_len, sel_count = sel
+    c, w = wl.chunk, wl.window
+    for l in range(wl.n_layers):
+        g = l // R
+        for b in range(wl.batch):
+            L = wl.seqlens[b]
+            P = L - w
+            kin = layers[l].seq_view(layers[l].k, b, wl.n_kv_heads, wl.head_dim)
+            vin = layers[l].seq_view(layers[l].v, b, wl.n_kv_heads, wl.head_dim)
+            ko, vo = H.out_view(prob, k_out[l], b), H.out_view(prob, v_out[l], b)
+            for h in range(wl.n_kv_heads):
+                m = int(sel_count[g, b, h])
+                ch = sel_chunk[g, b, h, :m].long()
+                ln = sel_len[g, b, h, :m].long()
+                starts = torch.repeat_interleave(ch * c, ln)
+                within = torch.arange(int(ln.sum()), device=DEV) - torch.repeat_interleave(torch.cumsum(ln, 0) - ln, ln)
+                idx = torch.cat([starts + within, torch.arange(P, L, device=DEV)])
+                # Gaussian inputs hold no NaN, so value equality of the stored type is bit equality
+                assert torch.equal(ko[h], kin[h].index_select(0, idx)), (l, b, h)
+                assert torch.equal(vo[h], vin[h].index_select(0, idx)), (l, b, h)
+
+
+def check_sampled_selections(lib, wl, layers, prob, sel, R, samples):
+    n_diff = 0
+    for (g, b, h) in samples:
+        leader = g * R
+        li = layers[leader]
+        q = W.tensor_bits(li.q[b, h * wl.group:(h + 1) * wl.group])                  # [g][w][d]
+        k = W.tensor_bits(li.seq_view(li.k, b, wl.n_kv_heads, wl.head_dim)[h:h + 1])  # [1][L][d]
+        P, nk = wl.seqlens[b] - wl.window, int(prob.n_keep[b])
+        o_cs, _ = orc.score(q, k, wl.window, wl.chunk)
+        o_sel = orc.chunk_topk(o_cs[0], P, wl.chunk, nk)
+        got = H.read_selection(prob, *sel, g)[b][h]
+        d = H.check_selection(got, o_sel, o_cs[0], P, wl.chunk, nk)
+        print(f"group {g} seq {b} head {h}: {d} chunks differ inside the tie band", flush=True)
+        n_diff += d
+    return n_diff
+
+
+def test_stack_128k_32_layers_reuse2(lib):
+    wl = W.get_workload("llama8b_128k_stack")
+    print("workload", wl.name, "R=2", flush=True)
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, 2)
+    check_structure_everywhere(wl, prob, sel, 2)
+    check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, 2)
+    check_sampled_selections(lib, wl, layers, prob, sel, 2, [(0, 0, 0), (7, 0, 5), (15, 0, 7)])
+    # chunk scores of two heads of one leader layer at full length
+    li = layers[14]
+    cs = torch.zeros((1, wl.n_kv_heads, prob.score_cap), dtype=torch.float32, device=DEV)
+    ws = torch.empty(lib.chunkkv_workspace_bytes(prob), dtype=torch.uint8, device=DEV)
+    lib.chunkkv_score(prob, li.q, li.k, cs, None, ws)
+    torch.cuda.synchronize()
+    for h in (1, 6):
+        q = W.tensor_bits(li.q[0, h * wl.group:(h + 1) * wl.group])
+        k = W.tensor_bits(li.k[0, h:h + 1])
+        o_cs, _ = orc.score(q, k, wl.window, wl.chunk)
+        err = H.rel_err(cs[0, h, :o_cs.shape[1]].cpu().numpy(), o_cs[0])
+        print(f"head {h}: max relative score error {err:.3e}", flush=True)
+        assert err <= H.REL_TOL
+
+
+@pytest.mark.parametrize("R", [1, 2])
+def test_stack_32k_32_layers(lib, R):
+    wl = W.get_workload("llama8b_32k_stack")
+    print("workload", wl.name, "R=", R, flush=True)
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, R)
+    check_structure_everywhere(wl, prob, sel, R)
+    check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, R)
+    G = (wl.n_layers + R - 1) // R
+    check_sampled_selections(lib, wl, layers, prob, sel, R, [(0, 0, 3), (G // 2, 0, 0), (G - 1, 0, 7)])
+
+
+def test_stack_128k_keep20(lib):
+    wl = W.get_workload("llama8b_128k_stack").with_(keep_pct=20, n_layers=8)
+    print("workload", wl.name, "20% 8 layers R=2", flush=True)
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, 2)
+    check_structure_everywhere(wl, prob, sel, 2)
+    check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, 2)
+    check_sampled_selections(lib, wl, layers, prob, sel, 2, [(3, 0, 2)])
+
+
+@pytest.mark.parametrize("chunk,pct,R", [(5, 10, 1), (10, 20, 2), (20, 30, 3), (5, 30, 2), (10, 10, 3), (20, 20, 1)])
+def test_ragged_batch_sweep(lib, chunk, pct, R):
+    # batch of 8 ragged sequences (4096..65536 tokens), 28 q / 4 kv heads, packed [sum L][Hkv][d];
+    # 6 of the 28 layers keep the run short, the launch shapes per layer are those of the full stack
+    wl = W.get_workload("ragged_b8").with_(chunk=chunk, keep_pct=pct, n_layers=6)
+    print("workload", wl.name, f"c={chunk} keep={pct}% R={R} L={wl.seqlens}", flush=True)
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, R)
+    check_structure_everywhere(wl, prob, sel, R)
+    check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, R)
+    short = int(np.argmin(wl.seqlens))
+    G = (wl.n_layers + R - 1) // R
+    check_sampled_selections(lib, wl, layers, prob, sel, R, [(0, short, 1), (G - 1, (short + 3) % 8, 3)])
+
+
+def test_ragged_batch_full_28_layers(lib):
+    wl = W.get_workload("ragged_b8")
+    print("workload", wl.name, "28 layers R=2", flush=True)
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, 2)
+    check_structure_everywhere(wl, prob, sel, 2)
+    check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, 2)
+    check_sampled_selections(lib, wl, layers, prob, sel, 2, [(13, int(np.argmin(wl.seqlens)), 0)])
