@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-layers", type=int, default=None)
     ap.add_argument("--no-r1", action="store_true", help="skip the R=1 comparison run")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
@@ -139,6 +141,13 @@ def main():
         kt = ckv.chunkkv_timing_end() if with_kernel_timing else None
         return dt / steps * 1e3, kt
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     run_main = make_run(R)
     ms, _ = timed(run_main, args.steps, args.warmup)
     # per-kernel durations: a second loop of the same steps with a HIP event pair around every launch
