@@ -112,6 +112,12 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
                            void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
                            int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 caches,
+ * at least 65 window rows per kv-head, chunk sizes whose pattern against 32-key blocks is short: 10, 20,
+ * 6, 12, powers of two, ...; not used when token_importance is requested) and a general two-pass one.
+ * chunkkv_set_single_pass(0) forces the two-pass kernels; the default is 1 (single pass where it applies). */
+int chunkkv_set_single_pass(int32_t enable);
+
 /* chunkkv_compress_stack scores the leader layers in sets and gathers each set's layers right after its
  * selection.  With chunkkv_set_overlap(1) the gather of a set is enqueued on an internal helper stream
  * (created on first use, default priority, ordered after `stream`'s prior work and joined back into it
@@ -125,7 +131,8 @@ int chunkkv_set_overlap(int32_t enable);
  * the calls above launch is bracketed by a HIP event pair on its stream (up to max_records launches).
  * chunkkv_timing_end waits for those events and returns, per kernel kind, the summed duration in
  * milliseconds and the number of launches:
- *   0 score pass 0 (softmax statistics)   1 statistics merge   2 score pass 1 (importance, chunk sums)
+ *   0 score pass 0 (softmax statistics) or the single-pass kernel   1 statistics merge
+ *   2 score pass 1 (importance, chunk sums) or the single-pass row reduction
  *   3 chunk sums for c larger than a key tile   4 chunk selection   5 compaction
  * total_ms and launches are host arrays of CHUNKKV_TIMING_KINDS entries.  Not thread-safe.          */
 #define CHUNKKV_TIMING_KINDS 6

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     chunkkv_compress_stack,
     chunkkv_score,
     chunkkv_set_overlap,
+    chunkkv_set_single_pass,
     chunkkv_status_string,
     chunkkv_timing_begin,
     chunkkv_timing_end,

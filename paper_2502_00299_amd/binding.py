@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_PKG, "libchunkkv.so")
 
 F32, BF16 = 0, 1
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
-           "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_set_overlap", "chunkkv_timing_begin",
+           "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_set_overlap", "chunkkv_set_single_pass",
+           "chunkkv_timing_begin",
            "chunkkv_timing_end")
 TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact")
 
@@ -201,6 +202,13 @@ def chunkkv_compress_stack(prob: Problem, reuse: int, q_obs: Sequence, k: Sequen
         _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
         "chunkkv_compress_stack")
+
+
+def chunkkv_set_single_pass(enable: bool) -> None:
+    lib = load_library()
+    lib.chunkkv_set_single_pass.restype = C.c_int
+    lib.chunkkv_set_single_pass.argtypes = [C.c_int32]
+    _check(lib.chunkkv_set_single_pass(1 if enable else 0), "chunkkv_set_single_pass")
 
 
 def chunkkv_set_overlap(enable: bool) -> None:

@@ -7,6 +7,7 @@
 namespace ckv {
 namespace {
 
+constexpr int kFusedTableLimit = 6144;   // bytes of LDS the single-pass kernel keeps for indicator fragments
 constexpr int kTargetWorkgroups = 2048;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
 // Key tiles (16 KB) one scoring launch set should hold.  Measured on MI355X: every extra dependent launch
 // costs ~30 us of idle GPU, more than splitting the stack into sets wins back, so one set it is.
@@ -18,7 +19,9 @@ struct Plan {
   int batch_leaders;  // leader layers scored per launch set (the unit that overlaps with compaction)
   int tpw0, tpw1, max_split0;
   int fuse_chunks;
-  size_t off_part, off_refs, off_scores, off_seloff, off_imp, total;
+  // single-pass path: usable for this problem?  geometry and workspace
+  int fused_ok, period_keys, unit_keys, n_periods, c_pad, tpw_f, max_split_f;
+  size_t off_part, off_refs, off_scores, off_seloff, off_imp, off_ebuf, off_mper, total;
 };
 
 // ---- optional per-kernel timing (chunkkv_timing_begin / chunkkv_timing_end) -----------------------
@@ -47,6 +50,7 @@ struct Timed {  // records an event pair around one launch when timing is on
 
 // ---- helper stream for overlapping the gather with scoring inside chunkkv_compress_stack ----------
 bool g_overlap_enabled = false;
+bool g_single_pass = true;  // use the single-pass scoring kernel where it applies
 struct Overlap {
   hipStream_t side = nullptr;
   static constexpr int kEvents = 128;
@@ -138,14 +142,50 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
     const int s = ceil_div(ceil_div(p->seqlen[b], TK), pl->tpw0);
     if (s > pl->max_split0) pl->max_split0 = s;
   }
+  // single-pass path (bf16, >= 65 window rows per kv-head, chunk pattern that fits the indicator table)
+  {
+    int gcd = 32, x = p->chunk;
+    while (x) { const int t = gcd % x; gcd = x; x = t; }
+    const int64_t pk = 32 / gcd * (int64_t)p->chunk;  // lcm(32, c)
+    const int64_t nslots = pk / p->chunk, phases = pk / 32;
+    pl->fused_ok = p->dtype == CHUNKKV_BF16 && pl->geom.wq == 4 && nslots <= 16 &&
+                   phases * 4 * (nslots + 1) * 16 <= kFusedTableLimit && pk <= 4096;
+    pl->period_keys = pl->unit_keys = pl->n_periods = pl->c_pad = 0;
+    pl->tpw_f = pl->max_split_f = 1;
+    if (pl->fused_ok) {
+      int g2 = TK, y = (int)pk;
+      while (y) { const int t = g2 % y; g2 = y; y = t; }
+      pl->period_keys = (int)pk;
+      pl->unit_keys = (int)(pk / g2 * TK);  // lcm(TK, pk)
+      int64_t units = 0;
+      for (int b = 0; b < p->batch; ++b) {
+        units += ceil_div(p->seqlen[b], pl->unit_keys);
+        const int np = ceil_div(p->seqlen[b], pl->period_keys);
+        if (np > pl->n_periods) pl->n_periods = np;
+      }
+      pl->c_pad = pl->n_periods * (int)nslots;
+      pl->tpw_f = (int)((units * heads + kTargetWorkgroups - 1) / kTargetWorkgroups);
+      if (pl->tpw_f < 1) pl->tpw_f = 1;
+      for (int b = 0; b < p->batch; ++b) {
+        const int sp = ceil_div(ceil_div(p->seqlen[b], pl->unit_keys), pl->tpw_f);
+        if (sp > pl->max_split_f) pl->max_split_f = sp;
+      }
+    }
+  }
   const size_t problems = (size_t)pl->n_leaders * p->batch * p->n_kv_heads;
+  const int max_split_any = pl->max_split0 > pl->max_split_f ? pl->max_split0 : pl->max_split_f;
   size_t off = 0;
-  pl->off_part = off;   off += align256(problems * pl->max_split0 * pl->rows_pad * sizeof(float2));
+  pl->off_part = off;   off += align256(problems * max_split_any * pl->rows_pad * sizeof(float2));
   pl->off_refs = off;   off += align256(problems * pl->rows_pad * sizeof(float));
   pl->off_scores = off; off += align256(problems * (size_t)p->score_cap * sizeof(float));
   pl->off_seloff = off; off += align256(problems * (size_t)p->sel_cap * sizeof(int32_t));
   pl->off_imp = off;
   if (!pl->fuse_chunks) off += align256(problems * (size_t)p->score_cap * p->chunk * sizeof(float));
+  pl->off_ebuf = pl->off_mper = off;
+  if (pl->fused_ok) {
+    pl->off_ebuf = off; off += align256(problems * (size_t)pl->n_periods * pl->rows_pad * 16 * sizeof(float));
+    pl->off_mper = off; off += align256(problems * (size_t)pl->n_periods * pl->rows_pad * sizeof(float));
+  }
   pl->total = off < 256 ? 256 : off;
   return CHUNKKV_OK;
 }
@@ -191,6 +231,26 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
       split1 = s1 > split1 ? s1 : split1;
     }
     int rc;
+    if (pl.fused_ok && g_single_pass && !token_imp) {
+      // one pass over K: per-(chunk, row) sums + running maxima, merge of the range statistics, weighted row sum
+      a.period_keys = pl.period_keys; a.unit_keys = pl.unit_keys; a.n_periods = pl.n_periods; a.c_pad = pl.c_pad;
+      a.e_buf = (float *)(ws + pl.off_ebuf);
+      a.m_period = (float *)(ws + pl.off_mper);
+      a.max_split = pl.max_split_f;
+      a.tiles_per_wg = pl.tpw_f;
+      int splitf = 1;
+      for (int i = 0; i < nb; ++i) {
+        const int sp = ceil_div(ceil_div(a.seq.seqlen[i], pl.unit_keys), pl.tpw_f);
+        splitf = sp > splitf ? sp : splitf;
+      }
+      { Timed t(kStats, s); rc = launch_score_fused(p->head_dim, pl.geom, a, dim3(splitf, nb * p->n_kv_heads, ng), s); }
+      if (rc) return rc;
+      { Timed t(kCombine, s); rc = launch_stats_combine(a, ng, nb, pl.unit_keys, s); }
+      if (rc) return rc;
+      { Timed t(kColsum, s); rc = launch_fused_scores(a, ng, nb, s); }
+      if (rc) return rc;
+      continue;
+    }
     a.tiles_per_wg = pl.tpw0;
     { Timed t(kStats, s); rc = launch_score_pass(0, p->dtype, p->head_dim, pl.geom, a, dim3(split0, nb * p->n_kv_heads, ng), s); }
     if (rc) return rc;
@@ -374,6 +434,11 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
     if (hipEventRecord(ov->next_event(), ov->side) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
     if (hipStreamWaitEvent(s, ov->last_event(), 0) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
   }
+  return CHUNKKV_OK;
+}
+
+int chunkkv_set_single_pass(int32_t enable) {
+  g_single_pass = enable != 0;
   return CHUNKKV_OK;
 }
 

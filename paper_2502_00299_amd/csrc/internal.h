@@ -45,6 +45,13 @@ struct ScoreArgs {
   float *token_imp;        // [leader][batch_total][Hkv][imp_pitch] or null
   int64_t imp_pitch;
   int32_t fuse_chunks;     // pass 1: 1 = super-tiles hold whole chunks and chunk sums are written
+  // single-pass path (score_fused.h)
+  int32_t period_keys;     // lcm(32, c): keys after which the key-block / chunk pattern repeats
+  int32_t unit_keys;       // lcm(tile keys, period_keys): granule of the key-range split
+  int32_t n_periods;       // pitch of m_period: max over sequences of ceil(L / period_keys)
+  int32_t c_pad;           // pitch of e_buf in chunks: n_periods * (period_keys / c)
+  float *e_buf;            // [problem][n_periods][rows_pad][16]  per-(chunk slot, row) sums of e
+  float *m_period;         // [problem][n_periods][rows_pad]  maximum those sums are relative to
 };
 
 struct TopkArgs {
@@ -98,6 +105,8 @@ int launch_score_pass(int pass, int dtype, int head_dim, const ScoreGeom &g, con
 int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slice, int tile_keys,
                          hipStream_t s);
 int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
+int launch_score_fused(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s);
 int launch_compact(int row_bytes, const CompactArgs &a, int n_layers_slice, int batch_slice,
                    int max_entries, hipStream_t s);

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
   const int last_keys = (span - (u1 - 1) * sstride) < sstride ? (span - (u1 - 1) * sstride) : sstride;
   const int nt = (u1 - 1 - u0) * spt + (last_keys + TK - 1) / TK;
   const int nblk = nt * KPW;  // key blocks this wavefront walks: block b = (tile b / KPW, kb = wk + (b % KPW) * WK)
-  auto tile_key0 = [&](int i) { return (u0 + i / spt) * sstride + (i % spt) * TK; };
+  auto tile_key0 = [&](int i) __attribute__((always_inline)) { return (u0 + i / spt) * sstride + (i % spt) * TK; };
 
   const char *qbase = (const char *)pick(a.q, z) + ((int64_t)(a.batch0 + bl) * a.n_q_heads + (int64_t)h * g) * w * ROWB;
   const char *kbase = (const char *)pick(a.k, z) + (pick(a.seq.kv_base, bl) + (int64_t)h * a.kv_stride_head) * ESZ;
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
     const int key = (wave * kLoadsPerWave + j) * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
     lane_off[j] = (uint32_t)(key * (int)ktok + ((segp ^ (key & 7)) * 16));
   }
-  auto issue_tile = [&](int i) {
+  auto issue_tile = [&](int i) __attribute__((always_inline)) {
     const int fk0 = tile_key0(i);
     char *slot = smem + (i % kRing) * kTileBytes;
     if (fk0 + TK <= L) {
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
     }
   };
   // tile i has landed once at most min(2, tiles issued after it) newer tile loads are outstanding
-  auto wait_tile = [&](int i) {
+  auto wait_tile = [&](int i) __attribute__((always_inline)) {
     const int newer = nt - 1 - i;
     if (newer >= 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kLoadsPerWave));
     else if (newer == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerWave));
@@ -192,13 +192,13 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
   }
 
   // lane's LDS address of fragment segment ks of key block b
-  auto frag_ptr = [&](int b, int ks) {
+  auto frag_ptr = [&](int b, int ks) __attribute__((always_inline)) {
     const char *buf = smem + ((b / KPW) % kRing) * kTileBytes;
     const int kb = wk + (b % KPW) * WK;
     return (const u32x4 *)(buf + ((kb * 32 + n) * NSEG + ((2 * ks + half) ^ (n & 7))) * 16);
   };
   // pass 0: does key block b touch keys a window row may not see (or keys past the sequence)?
-  auto block_masked = [&](int b) { return PASS == 0 && tile_key0(b / KPW) + TK > P; };
+  auto block_masked = [&](int b) __attribute__((always_inline)) { return PASS == 0 && tile_key0(b / KPW) + TK > P; };
 
   // exp/sum epilogue of key block b whose logits are in acc
   auto epilogue = [&](f32x16 (&acc)[NQW], int b, auto masked_c) {
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
   };
 
   // pass 1, after the epilogue of the last key block of a super-tile: importance, then chunk sums
-  auto flush_if_unit_done = [&](int b) {
+  auto flush_if_unit_done = [&](int b) __attribute__((always_inline)) {
     if constexpr (PASS == 1) {
       const int i = b / KPW;
       if ((b + 1) % KPW != 0 || !((i + 1) % spt == 0 || i + 1 == nt)) return;

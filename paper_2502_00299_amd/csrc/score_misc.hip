@@ -88,4 +88,64 @@ int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, 
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
+// Single-pass path, last step: score[chunk] = sum over rows of E[chunk][row] * exp2(m_period[row] - ref[row]).
+// One workgroup per (period, sequence, kv-head, leader), one thread per (padded) window row: a thread reads
+// its 16 slot values (64 contiguous bytes), weights them, and the 16 sums are reduced across the workgroup
+// in a fixed order.  grid: x = period, y = (sequence, kv-head), z = leader.
+__global__ void fused_scores_kernel(ScoreArgs a) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const int bl = blockIdx.y / a.n_kv_heads, h = blockIdx.y % a.n_kv_heads, z = blockIdx.z;
+  const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
+  const int P = pick(a.seq.seqlen, bl) - a.window, c = a.chunk;
+  const int C = (P + c - 1) / c, nslots = a.period_keys / c, period = blockIdx.x;
+  if ((int64_t)period * a.period_keys >= P) return;
+  const int nrows = (a.n_q_heads / a.n_kv_heads) * a.window;
+  __shared__ float s_red[8][16];
+  float v[16];
+  if (tid < nrows) {
+    const int64_t pr = ((int64_t)problem * a.n_periods + period) * a.rows_pad + tid;
+    const float wgt = exp2f(a.m_period[pr] - a.refs[problem * a.rows_pad + tid]);
+    const f32x4 *src = (const f32x4 *)(a.e_buf + pr * 16);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4 x = src[q];
+      v[4 * q] = x.x * wgt; v[4 * q + 1] = x.y * wgt; v[4 * q + 2] = x.z * wgt; v[4 * q + 3] = x.w * wgt;
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < 16; ++s) v[s] = 0.f;
+  }
+#pragma unroll
+  for (int s = 0; s < 16; ++s) {
+    for (int o = 32; o > 0; o >>= 1) v[s] += __shfl_xor(v[s], o);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int s = 0; s < 16; ++s) s_red[wave][s] = v[s];
+  }
+  __syncthreads();
+  if (tid < nslots) {
+    const int chunk = period * nslots + tid;
+    if (chunk < C) {
+      float sum = 0.f;
+      for (int i = 0; i < nwaves; ++i) sum += s_red[i][tid];
+      a.chunk_scores[problem * a.score_cap + chunk] = sum;
+    }
+  }
+}
+
+int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s) {
+  int max_periods = 0;
+  for (int b = 0; b < batch_slice; ++b) {
+    const int P = a.seq.seqlen[b] - a.window;
+    const int np = (P + a.period_keys - 1) / a.period_keys;
+    max_periods = np > max_periods ? np : max_periods;
+  }
+  if (max_periods == 0 || n_leaders_slice <= 0) return CHUNKKV_OK;
+  dim3 grid(max_periods, batch_slice * a.n_kv_heads, n_leaders_slice);
+  hipLaunchKernelGGL(fused_scores_kernel, grid, dim3(a.rows_pad), 0, s, a);
+  return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
+}
+
 }  // namespace ckv

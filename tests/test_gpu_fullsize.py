@@ -21,6 +21,15 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.fixture(params=["single_pass", "two_pass"], autouse=True)
+def scoring_path(request, lib):
+    """Every test runs with the single-pass scoring kernel enabled (used where it applies) and with
+    the two-pass kernels forced."""
+    lib.chunkkv_set_single_pass(request.param == "single_pass")
+    yield request.param
+    lib.chunkkv_set_single_pass(True)
+
+
 def run_stack(lib, wl, R, layers=None):
     N, B, Hk = wl.n_layers, wl.batch, wl.n_kv_heads
     layers = layers or [W.make_layer(wl, l, DEV) for l in range(N)]
