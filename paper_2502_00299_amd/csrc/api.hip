@@ -7,7 +7,7 @@
 namespace ckv {
 namespace {
 
-constexpr int kFusedTableLimit = 6144;   // bytes of LDS the single-pass kernel keeps for indicator fragments
+constexpr int kFusedTableLimit = 16384;  // bytes of LDS the single-pass kernel keeps for indicator fragments (2 KB per phase)
 constexpr int kTargetWorkgroups = 2048;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
 // Key tiles (16 KB) one scoring launch set should hold.  Measured on MI355X: every extra dependent launch
 // costs ~30 us of idle GPU, more than splitting the stack into sets wins back, so one set it is.
@@ -149,7 +149,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
     const int64_t pk = 32 / gcd * (int64_t)p->chunk;  // lcm(32, c)
     const int64_t nslots = pk / p->chunk, phases = pk / 32;
     pl->fused_ok = p->dtype == CHUNKKV_BF16 && pl->geom.wq == 4 && nslots <= 16 &&
-                   phases * 4 * (nslots + 1) * 16 <= kFusedTableLimit && pk <= 4096;
+                   phases * 2048 <= kFusedTableLimit;
     pl->period_keys = pl->unit_keys = pl->n_periods = pl->c_pad = 0;
     pl->tpw_f = pl->max_split_f = 1;
     if (pl->fused_ok) {
@@ -164,6 +164,10 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
         if (np > pl->n_periods) pl->n_periods = np;
       }
       pl->c_pad = pl->n_periods * (int)nslots;
+      // the kernels address E of one problem, and K of one (sequence, kv-head), with 32-bit byte offsets
+      if ((int64_t)pl->n_periods * pl->rows_pad * 64 >= (int64_t)1 << 32) pl->fused_ok = 0;
+      for (int b = 0; b < p->batch; ++b)
+        if (((int64_t)p->seqlen[b] + TK) * p->kv_stride_tok * 2 >= (int64_t)1 << 31) pl->fused_ok = 0;
       pl->tpw_f = (int)((units * heads + kTargetWorkgroups - 1) / kTargetWorkgroups);
       if (pl->tpw_f < 1) pl->tpw_f = 1;
       for (int b = 0; b < p->batch; ++b) {

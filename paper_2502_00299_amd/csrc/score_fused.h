@@ -28,7 +28,7 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kFusedTableBytes = 6144;  // indicator fragments: phases * 2 * 2 * (nslots + 1) * 16 B
+constexpr int kFusedTableBytes = 16384;  // indicator fragments: 2 KB per 32-key phase of a period, <= 8 phases
 constexpr int kFusedLdsBytes = kRing * kTileBytes + kFusedTableBytes;
 constexpr float kHalfShift = 12.f;      // e is scaled by 2^12 before the fp16 cast (<= 4096, denormals below 2^-26)
 
@@ -69,32 +69,24 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
   const int64_t ktok = a.kv_stride_tok * ESZ_BF16;
   const float c1 = a.scale_log2e;
 
-  // ---- K tiles: HBM -> LDS ring (see score_impl.h)
+  // ---- K tiles: HBM -> LDS ring (ring, swizzle and waits as in score_impl.h).  The loads are buffer
+  // loads with an LDS destination: the descriptor covers exactly the L rows of this (sequence, kv-head),
+  // so rows past the end of the sequence read as zero instead of being clamped.
+  const __amdgpu_buffer_rsrc_t krsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void *)kbase, 0, (int)((uint32_t)(L - 1) * (uint32_t)ktok + ROWB), 0x00020000);
+  uint32_t klane[kLoadsPerWave];  // lane's byte offset inside a tile: key row and swizzled 16-byte segment
+#pragma unroll
+  for (int j = 0; j < kLoadsPerWave; ++j) {
+    const int key = (wave * kLoadsPerWave + j) * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
+    klane[j] = (uint32_t)(key * (int)ktok + ((segp ^ (key & 7)) * 16));
+  }
   auto issue_tile = [&](int i) __attribute__((always_inline)) {
-    const int fk0 = range0 + i * TK;
+    const uint32_t tile_off = (uint32_t)(range0 + i * TK) * (uint32_t)ktok;
     char *slot = smem + (i % kRing) * kTileBytes;
-    if (fk0 + TK <= L) {
-      const char *tbase = kbase + (int64_t)fk0 * ktok;
 #pragma unroll
-      for (int j = 0; j < kLoadsPerWave; ++j) {
-        const int key = (wave * kLoadsPerWave + j) * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
-        const uint32_t lane_off = (uint32_t)(key * (int)ktok + ((segp ^ (key & 7)) * 16));
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(tbase + lane_off),
-                                         (__attribute__((address_space(3))) void *)(slot + (wave * kLoadsPerWave + j) * 1024),
-                                         16, 0, 0);
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < kLoadsPerWave; ++j) {
-        const int grp = wave * kLoadsPerWave + j;
-        const int key = grp * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
-        int gk = fk0 + key;
-        gk = gk < L ? gk : L - 1;
-        const char *src = kbase + (int64_t)gk * ktok + ((segp ^ (key & 7)) * 16);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(slot + grp * 1024), 16, 0, 0);
-      }
-    }
+    for (int j = 0; j < kLoadsPerWave; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void *)(slot + (wave * kLoadsPerWave + j) * 1024),
+                                               16, klane[j], tile_off, 0, 0);
   };
   // tile i has landed once at most `newer` tile loads issued after it are outstanding
   auto wait_tile = [&](int newer) __attribute__((always_inline)) {
@@ -106,14 +98,14 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
   for (int s = 0; s < kRing - 1; ++s)
     if (s < nt) issue_tile(s);
 
-  // ---- indicator fragments.  Entry (phase, j, kgroup, slot) holds, for the 8 k-positions e of MFMA j
-  // and lane half kgroup, 1.0 where the key of accumulator register 8j+e (block-relative key
-  // 8*((8j+e)/4) + 4*kgroup + (8j+e)%4) belongs to chunk slot `slot` of the period; slot == nslots is zero.
+  // ---- indicator fragments.  Entry (phase, kgroup, slot row, j) holds, for the 8 k-positions e of
+  // indicator MFMA j and lane half kgroup, 1.0 where the key of accumulator register 8j+e (block-relative
+  // key 8*((8j+e)/4) + 4*kgroup + (8j+e)%4) belongs to chunk slot `slot row` of the period.  Slot rows
+  // nslots..31 are zero; every lane reads an entry of its own (no two lanes share an address).
   {
-    const int entries = phases * 4 * (nslots + 1);
+    const int entries = phases * 128;
     for (int en = tid; en < entries; en += kThreads) {
-      const int slot = en % (nslots + 1), kg = (en / (nslots + 1)) & 1, j = (en / (2 * (nslots + 1))) & 1;
-      const int phase = en / (4 * (nslots + 1));
+      const int j = en & 1, slot = (en >> 1) & 31, kg = (en >> 6) & 1, phase = en >> 7;
       f16x8 v;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -124,10 +116,8 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
       *(f16x8 *)(s_tab + en * 16) = v;
     }
   }
-  // lane's table offset when its slot row n serves an even (rows 0..15) or an odd (rows 16..31) row block
-  const int lane_tab_even = (half * (nslots + 1) + (n < nslots ? n : nslots)) * 16;
-  const int lane_tab_odd = (half * (nslots + 1) + ((n >= 16 && n - 16 < nslots) ? n - 16 : nslots)) * 16;
-  const int tab_stride = 2 * (nslots + 1) * 16;  // bytes between consecutive (phase, j)
+  const uint32_t lane_tab = (uint32_t)(kRing * kTileBytes + (half * 32 + n) * 32);
+  constexpr uint32_t kPhaseBytes = 2048;
 
   // ---- window queries, running statistics
   u32x4 qf[NQW][NKS];
@@ -141,10 +131,10 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
     }
   }
   float m_run[NQW], l_run[NQW];  // l_run: this lane half's share of the row sum, relative to m_run
-  // Indicator accumulators.  A 32x32 tile has 32 slot rows but a period has at most 16 chunk slots, so two
-  // row blocks share one tile: block qi uses slot rows 16*(qi%2).., i.e. registers 8*(qi%2) + 0..7
-  // (register 8*(qi%2) + v <-> chunk slot 8*(v/4) + 4*half + v%4 for v < 8).
-  constexpr int NA = (NQW + 1) / 2;
+  // Indicator accumulators, one 32x32 tile per row block: a period has at most 16 chunk slots, so only
+  // registers 0..7 carry sums (register v <-> chunk slot 8*(v/4) + 4*half + v%4); the tile is kept whole
+  // so that every update is a whole-vector operation.
+  constexpr int NA = NQW;
   f32x16 acc2[NA];
 #pragma unroll
   for (int qi = 0; qi < NQW; ++qi) {
@@ -156,23 +146,69 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc2[i][v] = 0.f;
 
-  auto frag_ptr = [&](int b, int ks) __attribute__((always_inline)) {
-    const char *buf = smem + ((b / KBT) % kRing) * kTileBytes;
-    const int kb = b % KBT;
-    return (const u32x4 *)(buf + ((kb * 32 + n) * NSEG + ((2 * ks + half) ^ (n & 7))) * 16);
+  // ---- K operand fragments.  Lane n of a fragment read takes key row n of the block, 16-byte segment
+  // (2*ks + half) ^ (n & 7); ks and ks + 4 differ by 128 bytes, so four lane offsets serve all ks and the
+  // tile slot and the block within the tile are a wavefront-uniform term plus a constant.
+  uint32_t kaddr[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) kaddr[j] = (uint32_t)((n * NSEG + (((2 * j + half) ^ (n & 7)) & (NSEG - 1))) * 16);
+  auto frag = [&](uint32_t blk_off, int ks) __attribute__((always_inline)) {
+    return *(const u32x4 *)(smem + (kaddr[ks % 4] + blk_off + (uint32_t)((ks / 4) * 128)));
   };
-  auto block_key0 = [&](int b) __attribute__((always_inline)) { return range0 + b * 32; };
-  auto block_masked = [&](int b) __attribute__((always_inline)) { return block_key0(b) + 32 > P; };
 
-  // The pipeline advances in micro-steps t = b * NQW + qi (key block b, row block qi of this
-  // wavefront).  A micro-step finishes the previous one's logits in three parts:
-  // part 1: new running maximum of the row; rescale what is relative to the old one
-  auto update_max = [&](f32x16 &acc, int b, auto qi_c, auto masked_c) __attribute__((always_inline)) {
-    constexpr int QI = decltype(qi_c)::value;
+  // The pipeline advances in micro-steps: step (b, qi) is key block b against row block qi of this
+  // wavefront; inside a tile the step index idx = kb * NQW + qi is a compile-time constant.  The body of a
+  // step finishes the step's logits (running maximum, exponentials, indicator MFMAs) while the matrix
+  // cores compute the logits of the following step; K fragments are read just in time into a ring of four
+  // registers quads, each refilled four MFMAs ahead of its use.
+  constexpr int M = KBT * NQW;  // steps per tile (even)
+  u32x4 kf[4];
+  f32x16 accs[2];
+  // MFMAs ks0..ks1-1 of a step whose block sits at LDS offset off_s; off_n is the block of the step after it
+  auto mfma_part = [&](f32x16 &acc, auto qi_c, auto ks0_c, auto ks1_c, uint32_t off_s, uint32_t off_n)
+      __attribute__((always_inline)) {
+    constexpr int QI = decltype(qi_c)::value, KS0 = decltype(ks0_c)::value, KS1 = decltype(ks1_c)::value;
+#pragma unroll
+    for (int ks = KS0; ks < KS1; ++ks) {
+      if (ks == 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+      }
+      mma<DT>(acc, kf[ks % 4], qf[QI][ks]);  // D[key][row]
+      kf[ks % 4] = ks + 4 < NKS ? frag(off_s, ks + 4) : frag(off_n, ks + 4 - NKS);
+    }
+  };
+
+  int ph = 0;                      // key block within the period
+  int period = range0 / pk;        // period of the current key block
+  uint32_t tab_off = 0;            // ph * kPhaseBytes
+  // E and m_period of this problem (byte offsets inside stay below 2^32: n_periods * rows_pad * 64)
+  char *e_problem = (char *)a.e_buf + (int64_t)problem * a.n_periods * a.rows_pad * 64;
+  char *m_problem = (char *)a.m_period + (int64_t)problem * a.n_periods * a.rows_pad * 4;
+  const uint32_t lane_eoff = (uint32_t)((wq * NQW * 32 + n) * 64 + half * 16);
+  const uint32_t lane_moff = (uint32_t)((wq * NQW * 32 + n) * 4);
+
+  // CLEAN: the step belongs to a tile whose keys are all prefix keys and that is not among the last tiles
+  // of the range, so nothing has to be masked and the range cannot end here.
+  auto body = [&](int T, uint32_t toff, uint32_t toff_next, auto idx_c, auto masked_c, auto clean_c) __attribute__((always_inline)) {
+    constexpr bool CLEAN = decltype(clean_c)::value;
+    constexpr int IDX = decltype(idx_c)::value, KB = IDX / NQW, QI = IDX % NQW, PAR = IDX & 1;
     constexpr bool MASKED = decltype(masked_c)::value;
+    constexpr int I1 = (IDX + 1) % M, I2 = (IDX + 2) % M;       // the next two steps
+    constexpr bool W1 = IDX + 1 >= M, W2 = IDX + 2 >= M;        // ... lie in the next tile
+    constexpr int QI1 = I1 % NQW;
+    const uint32_t off1 = (W1 ? toff_next : toff) + (uint32_t)((I1 / NQW) * 32 * ROWB);
+    const uint32_t off2 = (W2 ? toff_next : toff) + (uint32_t)((I2 / NQW) * 32 * ROWB);
+    const int b = T * KBT + KB;
+    f32x16 &acc = accs[PAR];
+    constexpr int KSA = NKS >= 8 ? 2 : 1;  // MFMAs of the next step issued beside the maximum search
+
+    // part 1: new running maximum of the row
+    mfma_part(accs[PAR ^ 1], std::integral_constant<int, QI1>{}, std::integral_constant<int, 0>{},
+              std::integral_constant<int, KSA>{}, off1, off2);
+    const int k0 = range0 + b * 32 + 4 * half;
     if constexpr (MASKED) {
-      // only the last blocks of a sequence come here: the row's last visible key is recomputed
-      const int k0 = block_key0(b) + 4 * half;
+      // only the last blocks of a sequence come here: mask the keys behind the row's own position
       const int row = (wq * NQW + QI) * 32 + n;
       const int lim = P + (row < nrows ? row % w : 0);
 #pragma unroll
@@ -185,31 +221,36 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(bm), __float_as_uint(bm), false, false);
     bm = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
     const float m_new = fmaxf(m_run[QI], bm * c1);
-    // rescale what was accumulated relative to the old maximum (factor 1 when it did not grow);
-    // branch-free so that this, the MFMAs and the exponentials form one scheduled region
-    const float f = fast_exp2(m_run[QI] - m_new);
-#pragma unroll
-    for (int v = 0; v < 8; ++v) acc2[QI / 2][8 * (QI % 2) + v] *= f;
-    l_run[QI] *= f;
-    m_run[QI] = m_new;
-  };
-  // part 2 (inside the region): e = exp2(...), fp16 pack, two indicator MFMAs
-  auto accumulate = [&](f32x16 &acc, int b, auto qi_c, auto masked_c) __attribute__((always_inline)) {
-    constexpr int QI = decltype(qi_c)::value;
-    constexpr bool MASKED = decltype(masked_c)::value;
-    const int phase = b % phases;
-    const int lane_tab = QI % 2 ? lane_tab_odd : lane_tab_even;
-    const f16x8 ind0 = *(const f16x8 *)(s_tab + (phase * 2 + 0) * tab_stride + lane_tab);
-    const f16x8 ind1 = *(const f16x8 *)(s_tab + (phase * 2 + 1) * tab_stride + lane_tab);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    if constexpr (KSA > 1) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    // a maximum that grew (rare after the first blocks of a range): rescale what is relative to the old one
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run[QI]) != 0) {
+      const float f = fast_exp2(m_run[QI] - m_new);
+      acc2[QI] = acc2[QI] * f;
+      l_run[QI] *= f;
+      m_run[QI] = m_new;
+    }
+
+    // part 2: e = exp2(...), fp16 pack, two indicator MFMAs, beside the remaining MFMAs of the next step
+    mfma_part(accs[PAR ^ 1], std::integral_constant<int, QI1>{}, std::integral_constant<int, KSA>{},
+              std::integral_constant<int, NKS>{}, off1, off2);
+    const uint32_t taddr = lane_tab + tab_off;
+    const f16x8 ind0 = *(const f16x8 *)(smem + taddr);
+    const f16x8 ind1 = *(const f16x8 *)(smem + taddr + 16);
     const float off = kHalfShift - m_run[QI];
-    const int k0 = block_key0(b) + 4 * half;
-    // two halves of 8 logits: exp2, (masked: window keys go to the row sum only), fp16 pack, indicator MFMA
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       float e[8];
 #pragma unroll
       for (int v = 0; v < 8; ++v) e[v] = fast_exp2(__builtin_fmaf(acc[8 * j + v], c1, off));
       if constexpr (MASKED) {
+        // window keys count for the row sum but belong to no chunk
         float lw = 0.f;
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
@@ -226,120 +267,105 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
         const f16x2 h2 = __builtin_convertvector(f32x2{e[2 * p], e[2 * p + 1]}, f16x2);
         bj[2 * p] = h2[0]; bj[2 * p + 1] = h2[1];
       }
-      acc2[QI / 2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(j == 0 ? ind0 : ind1, bj, acc2[QI / 2], 0, 0, 0);
+      acc2[QI] = __builtin_amdgcn_mfma_f32_32x32x16_f16(j == 0 ? ind0 : ind1, bj, acc2[QI], 0, 0, 0);
     }
-  };
-  // part 3: at the end of a period (or of the range) write E and the maximum it is relative to.
-  // E layout [problem][period][row][16 slots]: registers 0..3 of a lane are slots 4*half + 0..3 and
-  // registers 4..7 slots 8 + 4*half + 0..3 (nslots <= 16), so a lane stores two 16-byte pieces.
-  auto flush_if_period_done = [&](int b, auto qi_c) __attribute__((always_inline)) {
-    constexpr int QI = decltype(qi_c)::value;
-    if ((b + 1) % phases != 0 && b + 1 != nblk) return;
-    const int period = block_key0(b) / pk;
-    const int row = (wq * NQW + QI) * 32 + n;
-    constexpr int A = QI / 2, R0 = 8 * (QI % 2);
-    f32x4 lo = {acc2[A][R0 + 0], acc2[A][R0 + 1], acc2[A][R0 + 2], acc2[A][R0 + 3]};
-    f32x4 hi = {acc2[A][R0 + 4], acc2[A][R0 + 5], acc2[A][R0 + 6], acc2[A][R0 + 7]};
-    l_run[QI] += ((lo.x + lo.y) + (lo.z + lo.w)) + ((hi.x + hi.y) + (hi.z + hi.w));
-    if (period < a.n_periods) {
-      const int64_t pr0 = ((int64_t)problem * a.n_periods + period) * a.rows_pad;  // wavefront-uniform
-      char *ebase = (char *)(a.e_buf + pr0 * 16);
-      const uint32_t eoff = (uint32_t)(row * 64 + half * 16);
-      *(f32x4 *)(ebase + eoff) = lo;
-      *(f32x4 *)(ebase + eoff + 32) = hi;
-      if (half == 0) *(float *)((char *)(a.m_period + pr0) + (uint32_t)(row * 4)) = m_run[QI];
-    }
+    if constexpr (!MASKED) {
+      constexpr int NM = NKS - KSA + 2;               // MFMAs of this region
+      constexpr int kValuPerMfma = (40 + NM - 1) / NM;  // 16 fma, 16 exp2, 8 packs, a few more
 #pragma unroll
-    for (int v = 0; v < 8; ++v) acc2[A][R0 + v] = 0.f;
-  };
-
-  // Operand fragments of K are read just in time: a ring of four 16-byte fragments, each refilled four
-  // MFMAs ahead of its use (same block, the next row block of the same key block, or the next key block).
-  // Because a tile is still being read while its last key block is processed, the slot refilled at a tile
-  // transition is the one of the tile before it.
-  u32x4 kf[4];
-  f32x16 accs[2];
-  auto micro = [&](int b, auto qi_c, auto par_c, auto has_prev_c, auto masked_c) __attribute__((always_inline)) {
-    constexpr int QI = decltype(qi_c)::value, PAR = decltype(par_c)::value;
-    constexpr bool HAS_PREV = decltype(has_prev_c)::value;
-    constexpr int PQI = QI > 0 ? QI - 1 : NQW - 1;
-    const int pb = QI > 0 ? b : b - 1;
-    if constexpr (QI == 0) {
-      if ((b + 1) % KBT == 0 && (b + 1) / KBT < nt) {
-        const int inext = (b + 1) / KBT;              // tiles <= inext + 1 have been issued
-        wait_tile(inext + 1 < nt ? 1 : 0);
-        lds_barrier();  // tile inext is in LDS; every wavefront is done with tile inext - 2
-        if (inext + 2 < nt) issue_tile(inext + 2);  // into the slot of tile inext - 2
-      }
-    }
-    const int nb = QI == NQW - 1 ? (b + 1 < nblk ? b + 1 : b) : b;  // key block of the next micro-step
-#pragma unroll
-    for (int v = 0; v < 16; ++v) accs[PAR][v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      mma<DT>(accs[PAR], kf[ks % 4], qf[QI][ks]);  // D[key][row]
-      kf[ks % 4] = ks + 4 < NKS ? *frag_ptr(b, ks + 4) : *frag_ptr(nb, ks + 4 - NKS);
-    }
-    if constexpr (HAS_PREV) {
-      update_max(accs[PAR ^ 1], pb, std::integral_constant<int, PQI>{}, masked_c);
-      accumulate(accs[PAR ^ 1], pb, std::integral_constant<int, PQI>{}, masked_c);
-      constexpr int kValuPerMfma = (16 * 4) / NKS + 1;
-#pragma unroll
-      for (int r = 0; r < NKS; ++r) {
+      for (int r = 0; r < NM; ++r) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-      flush_if_period_done(pb, std::integral_constant<int, PQI>{});
     }
-  };
-  auto run_micro = [&](int b, auto qi_c, auto par_c) __attribute__((always_inline)) {
-    constexpr int QI = decltype(qi_c)::value;
-    if (block_masked(QI > 0 ? b : b - 1)) micro(b, qi_c, par_c, std::true_type{}, std::true_type{});
-    else micro(b, qi_c, par_c, std::true_type{}, std::false_type{});
-  };
-  // all row blocks of key block b; PAR0 = parity of micro-step b * NQW
-  auto run_block = [&](int b, auto par0_c) __attribute__((always_inline)) {
-    constexpr int PAR0 = decltype(par0_c)::value;
-    run_micro(b, std::integral_constant<int, 0>{}, std::integral_constant<int, PAR0>{});
-    if constexpr (NQW > 1) run_micro(b, std::integral_constant<int, 1>{}, std::integral_constant<int, PAR0 ^ 1>{});
-    if constexpr (NQW > 2) {
-      run_micro(b, std::integral_constant<int, 2>{}, std::integral_constant<int, PAR0>{});
-      run_micro(b, std::integral_constant<int, 3>{}, std::integral_constant<int, PAR0 ^ 1>{});
+
+    // part 3: at the end of a period (or of the range) write E and the maximum it is relative to.
+    // E layout [problem][period][row][16 slots]: registers 0..3 of a lane are slots 4*half + 0..3 and
+    // registers 4..7 slots 8 + 4*half + 0..3 (nslots <= 16), so a lane stores two 16-byte pieces.
+    if (ph == phases - 1 || (!CLEAN && b == nblk - 1)) {
+      f32x4 lo = {acc2[QI][0], acc2[QI][1], acc2[QI][2], acc2[QI][3]};
+      f32x4 hi = {acc2[QI][4], acc2[QI][5], acc2[QI][6], acc2[QI][7]};
+      l_run[QI] += ((lo.x + lo.y) + (lo.z + lo.w)) + ((hi.x + hi.y) + (hi.z + hi.w));
+      if (period < a.n_periods) {
+        const uint32_t prow = (uint32_t)period * (uint32_t)a.rows_pad + (uint32_t)(QI * 32);  // wavefront-uniform
+        const uint32_t eoff = prow * 64u + lane_eoff;
+        *(f32x4 *)(e_problem + eoff) = lo;
+        *(f32x4 *)(e_problem + eoff + 32) = hi;
+        if (half == 0) *(float *)(m_problem + (prow * 4u + lane_moff)) = m_run[QI];
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc2[QI][v] = 0.f;
+    }
+    if constexpr (QI == NQW - 1) {
+      // the key block is done: advance the period phase
+      const bool wrap = ph == phases - 1;
+      ph = wrap ? 0 : ph + 1;
+      tab_off = wrap ? 0u : tab_off + kPhaseBytes;
+      period += wrap ? 1 : 0;
     }
   };
 
   wait_tile(nt - 1 < 2 ? nt - 1 : 2);  // tiles 0..2 issued
   lds_barrier();                        // tile 0 and the indicator table are in LDS
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) kf[ks] = *frag_ptr(0, ks % NKS);
-  // key block 0: its first micro-step has no predecessor
-  micro(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::false_type{}, std::false_type{});
-  if constexpr (NQW > 1) run_micro(0, std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
-  if constexpr (NQW > 2) {
-    run_micro(0, std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
-    run_micro(0, std::integral_constant<int, 3>{}, std::integral_constant<int, 1>{});
-  }
-  for (int b = 1; b < nblk; b += 2) {
-    run_block(b, std::integral_constant<int, NQW & 1>{});          // odd b: parity of b * NQW is NQW & 1
-    if (b + 1 < nblk) run_block(b + 1, std::integral_constant<int, 0>{});
-  }
+  for (int ks = 0; ks < 4; ++ks) kf[ks] = frag(0u, ks % NKS);
   {
-    // the last micro-step (nblk-1, NQW-1) still owes its epilogue
-    constexpr int LQ = NQW - 1;
-    const int lb = nblk - 1;
-    auto finish = [&](f32x16 &last) __attribute__((always_inline)) {
-      if (block_masked(lb)) {
-        update_max(last, lb, std::integral_constant<int, LQ>{}, std::true_type{});
-        accumulate(last, lb, std::integral_constant<int, LQ>{}, std::true_type{});
-      } else {
-        update_max(last, lb, std::integral_constant<int, LQ>{}, std::false_type{});
-        accumulate(last, lb, std::integral_constant<int, LQ>{}, std::false_type{});
+    // logits of step 0; the step after it is in tile 0 as well
+    constexpr uint32_t kOff1 = (uint32_t)((1 / NQW) * 32 * ROWB);
+    mfma_part(accs[0], std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{},
+              std::integral_constant<int, NKS>{}, 0u, kOff1);
+  }
+  // Tiles that need no checks: all their keys are prefix keys and three more tiles follow in the range.
+  int n_clean = (P - range0) / TK;
+  n_clean = n_clean < nt - 3 ? n_clean : nt - 3;
+  n_clean = n_clean > 0 ? n_clean : 0;
+  auto for_steps = [&](auto f) __attribute__((always_inline)) {
+    f(std::integral_constant<int, 0>{});
+    f(std::integral_constant<int, 1>{});
+    if constexpr (M > 2) { f(std::integral_constant<int, 2>{}); f(std::integral_constant<int, 3>{}); }
+    if constexpr (M > 4) {
+      f(std::integral_constant<int, 4>{}); f(std::integral_constant<int, 5>{});
+      f(std::integral_constant<int, 6>{}); f(std::integral_constant<int, 7>{});
+    }
+    if constexpr (M > 8) {
+      f(std::integral_constant<int, 8>{}); f(std::integral_constant<int, 9>{});
+      f(std::integral_constant<int, 10>{}); f(std::integral_constant<int, 11>{});
+      f(std::integral_constant<int, 12>{}); f(std::integral_constant<int, 13>{});
+      f(std::integral_constant<int, 14>{}); f(std::integral_constant<int, 15>{});
+    }
+    static_assert(M <= 16, "steps per tile");
+  };
+  int T = 0;
+  for (; T < n_clean; ++T) {
+    const uint32_t toff = (uint32_t)((T % kRing) * kTileBytes), toff_next = (uint32_t)(((T + 1) % kRing) * kTileBytes);
+    for_steps([&](auto idx_c) __attribute__((always_inline)) {
+      constexpr int IDX = decltype(idx_c)::value;
+      if constexpr (IDX == M - 2) {
+        // the refills of this step start to read tile T + 1
+        wait_tile(1);      // tiles <= T + 2 have been issued
+        lds_barrier();     // tile T + 1 is in LDS; every wavefront is done with tile T - 1
+        issue_tile(T + 3);
       }
-    };
-    if (((lb * NQW + LQ) & 1) == 0) finish(accs[0]);
-    else finish(accs[1]);
-    flush_if_period_done(lb, std::integral_constant<int, LQ>{});
+      body(T, toff, toff_next, idx_c, std::false_type{}, std::true_type{});
+    });
+  }
+  for (; T < nt; ++T) {
+    const uint32_t toff = (uint32_t)((T % kRing) * kTileBytes), toff_next = (uint32_t)(((T + 1) % kRing) * kTileBytes);
+    const int nb_t = nblk - T * KBT;  // key blocks of this tile that hold keys of the sequence (>= 1)
+    for_steps([&](auto idx_c) __attribute__((always_inline)) {
+      constexpr int IDX = decltype(idx_c)::value;
+      if (IDX / NQW >= nb_t) return;
+      if constexpr (IDX == M - 2) {
+        if (T + 1 < nt) {
+          wait_tile(T + 2 < nt ? 1 : 0);
+          lds_barrier();
+          if (T + 3 < nt) issue_tile(T + 3);
+        }
+      }
+      if (range0 + (T * KBT + IDX / NQW) * 32 + 32 > P) body(T, toff, toff_next, idx_c, std::true_type{}, std::false_type{});
+      else body(T, toff, toff_next, idx_c, std::false_type{}, std::false_type{});
+    });
   }
 
   // per-range (max, sum) of every row for the merge kernel; sums carry the 2^kHalfShift scale throughout
@@ -363,7 +389,8 @@ int launch_fused_cfg(const ScoreArgs &a, dim3 grid, hipStream_t s) {
       return CHUNKKV_ERR_LAUNCH;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(kThreads), kFusedLdsBytes, s, a);
+  const int lds_bytes = kRing * kTileBytes + a.period_keys / 32 * 2048;  // ring + indicator table
+  hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds_bytes, s, a);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 

@@ -89,49 +89,61 @@ int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, 
 }
 
 // Single-pass path, last step: score[chunk] = sum over rows of E[chunk][row] * exp2(m_period[row] - ref[row]).
-// One workgroup per (period, sequence, kv-head, leader), one thread per (padded) window row: a thread reads
-// its 16 slot values (64 contiguous bytes), weights them, and the 16 sums are reduced across the workgroup
-// in a fixed order.  grid: x = period, y = (sequence, kv-head), z = leader.
-__global__ void fused_scores_kernel(ScoreArgs a) {
+// A workgroup of 256 threads takes kPeriodsPerGroup consecutive periods of one problem.  The E block of a
+// period is rows_pad x 16 floats, contiguous; thread t reads the 16-byte pieces t, t + 256, ... (row
+// t/4 + 64*i, chunk slots 4*(t%4)..+3), so every load instruction of a wavefront covers 1 KB.  The four
+// partial sums of a thread are reduced over the threads of equal t%4, in a fixed order.
+// grid: x = period group, y = (sequence, kv-head), z = leader.
+constexpr int kPeriodsPerGroup = 8;
+constexpr int kMaxRowPasses = kMaxRows / 64;
+
+__global__ __launch_bounds__(256) void fused_scores_kernel(ScoreArgs a) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bl = blockIdx.y / a.n_kv_heads, h = blockIdx.y % a.n_kv_heads, z = blockIdx.z;
   const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
   const int P = pick(a.seq.seqlen, bl) - a.window, c = a.chunk;
-  const int C = (P + c - 1) / c, nslots = a.period_keys / c, period = blockIdx.x;
-  if ((int64_t)period * a.period_keys >= P) return;
+  const int C = (P + c - 1) / c, nslots = a.period_keys / c;
+  const int np = (P + a.period_keys - 1) / a.period_keys;
+  const int p0 = blockIdx.x * kPeriodsPerGroup;
+  if (p0 >= np) return;
+  const int p1 = p0 + kPeriodsPerGroup < np ? p0 + kPeriodsPerGroup : np;
   const int nrows = (a.n_q_heads / a.n_kv_heads) * a.window;
-  __shared__ float s_red[8][16];
-  float v[16];
-  if (tid < nrows) {
-    const int64_t pr = ((int64_t)problem * a.n_periods + period) * a.rows_pad + tid;
-    const float wgt = exp2f(a.m_period[pr] - a.refs[problem * a.rows_pad + tid]);
+  const int passes = a.rows_pad / 64;
+  __shared__ float s_red[kPeriodsPerGroup][4][16];
+
+  float ref[kMaxRowPasses];
+#pragma unroll
+  for (int i = 0; i < kMaxRowPasses; ++i) {
+    const int row = (tid >> 2) + 64 * i;
+    ref[i] = (i < passes && row < nrows) ? a.refs[problem * a.rows_pad + row] : 3.0e38f;  // weight 0 for padding rows
+  }
+  for (int period = p0; period < p1; ++period) {
+    const int64_t pr = ((int64_t)problem * a.n_periods + period) * a.rows_pad;
     const f32x4 *src = (const f32x4 *)(a.e_buf + pr * 16);
+    const float *mp = a.m_period + pr;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const f32x4 x = src[q];
-      v[4 * q] = x.x * wgt; v[4 * q + 1] = x.y * wgt; v[4 * q + 2] = x.z * wgt; v[4 * q + 3] = x.w * wgt;
+    for (int i = 0; i < kMaxRowPasses; ++i) {
+      if (i < passes) {
+        const float wgt = exp2f(mp[(tid >> 2) + 64 * i] - ref[i]);
+        const f32x4 x = src[tid + 256 * i];
+        v += x * wgt;
+      }
     }
-  } else {
 #pragma unroll
-    for (int s = 0; s < 16; ++s) v[s] = 0.f;
-  }
-#pragma unroll
-  for (int s = 0; s < 16; ++s) {
-    for (int o = 32; o > 0; o >>= 1) v[s] += __shfl_xor(v[s], o);
-  }
-  if (lane == 0) {
-#pragma unroll
-    for (int s = 0; s < 16; ++s) s_red[wave][s] = v[s];
+    for (int o = 4; o < 64; o <<= 1) {
+      v.x += __shfl_xor(v.x, o); v.y += __shfl_xor(v.y, o); v.z += __shfl_xor(v.z, o); v.w += __shfl_xor(v.w, o);
+    }
+    if (lane < 4) *(f32x4 *)&s_red[period - p0][wave][4 * lane] = v;
   }
   __syncthreads();
-  if (tid < nslots) {
-    const int chunk = period * nslots + tid;
-    if (chunk < C) {
-      float sum = 0.f;
-      for (int i = 0; i < nwaves; ++i) sum += s_red[i][tid];
-      a.chunk_scores[problem * a.score_cap + chunk] = sum;
-    }
+  if (tid < kPeriodsPerGroup * 16) {
+    const int pi = tid >> 4, slot = tid & 15, period = p0 + pi;
+    const int chunk = period * nslots + slot;
+    if (period < p1 && slot < nslots && chunk < C)
+      a.chunk_scores[problem * a.score_cap + chunk] =
+          (s_red[pi][0][slot] + s_red[pi][1][slot]) + (s_red[pi][2][slot] + s_red[pi][3][slot]);
   }
 }
 
@@ -143,8 +155,9 @@ int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice
     max_periods = np > max_periods ? np : max_periods;
   }
   if (max_periods == 0 || n_leaders_slice <= 0) return CHUNKKV_OK;
-  dim3 grid(max_periods, batch_slice * a.n_kv_heads, n_leaders_slice);
-  hipLaunchKernelGGL(fused_scores_kernel, grid, dim3(a.rows_pad), 0, s, a);
+  if (a.rows_pad % 64 != 0 || a.rows_pad > kMaxRows) return CHUNKKV_ERR_UNSUPPORTED;
+  dim3 grid((max_periods + kPeriodsPerGroup - 1) / kPeriodsPerGroup, batch_slice * a.n_kv_heads, n_leaders_slice);
+  hipLaunchKernelGGL(fused_scores_kernel, grid, dim3(256), 0, s, a);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
