@@ -30,7 +30,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kFusedTableBytes = 16384;  // indicator fragments: 2 KB per 32-key phase of a period, <= 8 phases
 constexpr int kFusedLdsBytes = kRing * kTileBytes + kFusedTableBytes;
-constexpr float kHalfShift = 12.f;      // e is scaled by 2^12 before the fp16 cast (<= 4096, denormals below 2^-26)
+constexpr float kHalfShift = 12.f;      // e is scaled by 2^12 before the fp16 cast (denormals below 2^-26)
+constexpr float kLazy = 2.f;            // slack of the running reference, log2 units
 
 template <int HD, int NQW>
 __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kernel(ScoreArgs a) {
@@ -203,6 +204,11 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
     f32x16 &acc = accs[PAR];
     constexpr int KSA = NKS >= 8 ? 2 : 1;  // MFMAs of the next step issued beside the maximum search
 
+    // indicator fragments of this key block, needed in part 2
+    const uint32_t taddr = lane_tab + tab_off;
+    const f16x8 ind0 = *(const f16x8 *)(smem + taddr);
+    const f16x8 ind1 = *(const f16x8 *)(smem + taddr + 16);
+
     // part 1: new running maximum of the row
     mfma_part(accs[PAR ^ 1], std::integral_constant<int, QI1>{}, std::integral_constant<int, 0>{},
               std::integral_constant<int, KSA>{}, off1, off2);
@@ -214,13 +220,18 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[v] = k0 + 8 * (v / 4) + (v % 4) <= lim ? acc[v] : -3.0e38f;
     }
-    float bm = acc[0];
-#pragma unroll
-    for (int v = 1; v < 16; ++v) bm = fmaxf(bm, acc[v]);
+    // block maximum as a shallow tree
+    const float t0 = fmaxf(fmaxf(acc[0], acc[1]), acc[2]), t1 = fmaxf(fmaxf(acc[3], acc[4]), acc[5]);
+    const float t2 = fmaxf(fmaxf(acc[6], acc[7]), acc[8]), t3 = fmaxf(fmaxf(acc[9], acc[10]), acc[11]);
+    const float t4 = fmaxf(fmaxf(acc[12], acc[13]), acc[14]);
+    float bm = fmaxf(fmaxf(fmaxf(t0, t1), t2), fmaxf(fmaxf(t3, t4), acc[15]));
     // both lane halves of a row share one reference: exchange across the halves without LDS
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(bm), __float_as_uint(bm), false, false);
     bm = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-    const float m_new = fmaxf(m_run[QI], bm * c1);
+    // The reference m_run need not be the exact maximum: it moves only when the block maximum exceeds it
+    // by more than kLazy (then it is set one above the maximum), so e stays below 2^kLazy and the fp16
+    // products below 2^(kHalfShift + kLazy); after the first blocks of a range this is rare.
+    const float cand = __builtin_fmaf(bm, c1, -kLazy);
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -229,8 +240,8 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
       __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    // a maximum that grew (rare after the first blocks of a range): rescale what is relative to the old one
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run[QI]) != 0) {
+    if (__builtin_amdgcn_ballot_w64(cand > m_run[QI]) != 0) {
+      const float m_new = cand > m_run[QI] ? cand + (kLazy + 1.f) : m_run[QI];
       const float f = fast_exp2(m_run[QI] - m_new);
       acc2[QI] = acc2[QI] * f;
       l_run[QI] *= f;
@@ -240,9 +251,6 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
     // part 2: e = exp2(...), fp16 pack, two indicator MFMAs, beside the remaining MFMAs of the next step
     mfma_part(accs[PAR ^ 1], std::integral_constant<int, QI1>{}, std::integral_constant<int, KSA>{},
               std::integral_constant<int, NKS>{}, off1, off2);
-    const uint32_t taddr = lane_tab + tab_off;
-    const f16x8 ind0 = *(const f16x8 *)(smem + taddr);
-    const f16x8 ind1 = *(const f16x8 *)(smem + taddr + 16);
     const float off = kHalfShift - m_run[QI];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -294,8 +302,7 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
         *(f32x4 *)(e_problem + eoff + 32) = hi;
         if (half == 0) *(float *)(m_problem + (prow * 4u + lane_moff)) = m_run[QI];
       }
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc2[QI][v] = 0.f;
+      acc2[QI] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     }
     if constexpr (QI == NQW - 1) {
       // the key block is done: advance the period phase
