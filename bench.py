@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-layers", type=int, default=None)
     ap.add_argument("--no-r1", action="store_true", help="skip the R=1 comparison run")
+    ap.add_argument("--overlap", type=int, default=0,
+                    help="k > 0: score the leader layers in k sets and gather each set on a helper stream")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -95,6 +97,7 @@ def main():
 
     import paper_2502_00299_amd as ckv
     ckv.load_library()
+    ckv.chunkkv_set_overlap(args.overlap)
     dev = "cuda:0"
     wl = W.get_workload(args.workload)
     if args.keep_pct is not None:

@@ -113,18 +113,20 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
                            int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 caches,
- * at least 65 window rows per kv-head, chunk sizes whose pattern against 32-key blocks is short: 10, 20,
- * 6, 12, powers of two, ...; not used when token_importance is requested) and a general two-pass one.
+ * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
+ * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a
+ * general two-pass one.
  * chunkkv_set_single_pass(0) forces the two-pass kernels; the default is 1 (single pass where it applies). */
 int chunkkv_set_single_pass(int32_t enable);
 
-/* chunkkv_compress_stack scores the leader layers in sets and gathers each set's layers right after its
- * selection.  With chunkkv_set_overlap(1) the gather of a set is enqueued on an internal helper stream
- * (created on first use, default priority, ordered after `stream`'s prior work and joined back into it
- * with events before the call returns) so that it can run beside the scoring of the next set.  The
- * default is 0: everything on `stream` (on MI355X the scoring kernels leave no register room for
- * co-resident gather wavefronts, so the helper stream does not pay off yet).                        */
-int chunkkv_set_overlap(int32_t enable);
+/* chunkkv_compress_stack normally scores all leader layers with one launch per kernel, selects, then
+ * gathers all layers.  chunkkv_set_overlap(k) with k > 0 splits the leader layers into k sets and
+ * enqueues the gather of a set on an internal helper stream (created on first use, default priority,
+ * ordered after `stream`'s prior work and joined back into it with events before the call returns) so
+ * that it can run beside the scoring of the next set.  The default is 0: one set, everything on
+ * `stream` (on MI355X the scoring kernels leave no register room for co-resident gather wavefronts and
+ * every extra dependent launch costs tens of microseconds, so the split does not pay off).         */
+int chunkkv_set_overlap(int32_t sets);
 
 /* Measurement aid (the per-kernel durations the roofline figures need; Algorithm 2's T_compress and
  * T_select are the scoring+selection and the gather durations).  Between begin and end every kernel

@@ -215,7 +215,7 @@ def chunkkv_set_overlap(enable: bool) -> None:
     lib = load_library()
     lib.chunkkv_set_overlap.restype = C.c_int
     lib.chunkkv_set_overlap.argtypes = [C.c_int32]
-    _check(lib.chunkkv_set_overlap(1 if enable else 0), "chunkkv_set_overlap")
+    _check(lib.chunkkv_set_overlap(int(enable)), "chunkkv_set_overlap")
 
 
 def chunkkv_timing_begin(max_records: int = 4096) -> None:

@@ -49,7 +49,7 @@ struct Timed {  // records an event pair around one launch when timing is on
 };
 
 // ---- helper stream for overlapping the gather with scoring inside chunkkv_compress_stack ----------
-bool g_overlap_enabled = false;
+int g_overlap_sets = 0;  // 0: one set, no helper stream; k > 0: k sets of leader layers, gather on the helper stream
 bool g_single_pass = true;  // use the single-pass scoring kernel where it applies
 struct Overlap {
   hipStream_t side = nullptr;
@@ -127,6 +127,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   // few enough that compaction of one set overlaps scoring of the next; sets are balanced in size
   int64_t per_leader = tiles0 * p->n_kv_heads;
   int gb = (int)((kTilesPerLaunch + per_leader - 1) / (per_leader > 0 ? per_leader : 1));
+  if (g_overlap_sets > 0) gb = ceil_div(pl->n_leaders, g_overlap_sets);
   if (gb < 1) gb = 1;
   if (gb > pl->n_leaders) gb = pl->n_leaders;
   if (gb > kMaxLayersPerLaunch) gb = kMaxLayersPerLaunch;
@@ -410,7 +411,7 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
   // Algorithm 2: leader layers (l % reuse == 0) are scored and selected set by set on `stream`; the
   // gather of a set's layers (pure HBM traffic) runs on the helper stream while the next set is
   // scored (matrix/vector bound), and is joined back into `stream` before the call returns.
-  Overlap *ov = g_overlap_enabled ? overlap_state() : nullptr;
+  Overlap *ov = g_overlap_sets > 0 ? overlap_state() : nullptr;
   if (ov && hipEventRecord(ov->next_event(), s) == hipSuccess) {
     (void)hipStreamWaitEvent(ov->side, ov->last_event(), 0);  // helper stream starts after the caller's prior work
   } else {
@@ -446,8 +447,8 @@ int chunkkv_set_single_pass(int32_t enable) {
   return CHUNKKV_OK;
 }
 
-int chunkkv_set_overlap(int32_t enable) {
-  g_overlap_enabled = enable != 0;
+int chunkkv_set_overlap(int32_t sets) {
+  g_overlap_sets = sets < 0 ? 0 : sets;
   return CHUNKKV_OK;
 }
 

@@ -10,6 +10,8 @@
 
 namespace ckv {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 template <int NSEG>  // 16-byte segments per row
 __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -79,21 +81,24 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a) {
     const int half = len * NSEG, total = 2 * half;
     // segment u of the entry: K rows first, then V rows; lanes past the end re-read the last
     // segment and store nothing
-    auto src_of = [&](int u) -> const uint4 * {
+    auto src_of = [&](int u) -> const u32x4 * {
       u = u < total ? u : total - 1;
       const int t = u >= half, uu = u - t * half;
-      return (const uint4 *)((t ? vin : kin) + (int64_t)(src_row + uu / NSEG) * in_tok + (uu % NSEG) * 16);
+      return (const u32x4 *)((t ? vin : kin) + (int64_t)(src_row + uu / NSEG) * in_tok + (uu % NSEG) * 16);
     };
-    auto dst_of = [&](int u) -> uint4 * {
+    auto dst_of = [&](int u) -> u32x4 * {
       const int t = u >= half, uu = u - t * half;
-      return (uint4 *)((t ? vout : kout) + (int64_t)(dst_row + uu / NSEG) * out_tok + (uu % NSEG) * 16);
+      return (u32x4 *)((t ? vout : kout) + (int64_t)(dst_row + uu / NSEG) * out_tok + (uu % NSEG) * 16);
     };
-    for (int base = lane; base < total; base += 64 * 4) {
-      const uint4 r0 = *src_of(base), r1 = *src_of(base + 64), r2 = *src_of(base + 128), r3 = *src_of(base + 192);
+    // five 1 KB loads in flight: one pass for a chunk of 10 rows of 128 16-bit values (K and V)
+    for (int base = lane; base < total; base += 64 * 5) {
+      const u32x4 r0 = *src_of(base), r1 = *src_of(base + 64), r2 = *src_of(base + 128), r3 = *src_of(base + 192);
+      const u32x4 r4 = *src_of(base + 256);
       *dst_of(base) = r0;
       if (base + 64 < total) *dst_of(base + 64) = r1;
       if (base + 128 < total) *dst_of(base + 128) = r2;
       if (base + 192 < total) *dst_of(base + 192) = r3;
+      if (base + 256 < total) *dst_of(base + 256) = r4;
     }
   }
 }

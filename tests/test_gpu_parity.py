@@ -55,6 +55,17 @@ SCORE_CASES = {
     "bf16_rows224_g7": small("ragged_b8", seqlens=(2049, 517), n_spans=(10, 2), n_layers=1),
     "bf16_rows256_w64": small("llama8b_128k_stack", seqlens=(4100,), n_spans=(20,), n_layers=1),
     "bf16_rows512": small("llama8b_8k", n_q_heads=16, n_kv_heads=2, window=64, seqlens=(700,), n_spans=(4,)),
+    # single-pass kernel geometries: head_dim 64 with 1, 2 and 4 row blocks per wavefront, and chunk sizes
+    # whose period against 32-key blocks is 1, 2, 3, 5 and 7 blocks long
+    "bf16_d64_rows128_c12": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, head_dim=64, window=32, seqlens=(1531,),
+                                  chunk=12, n_spans=(6,)),
+    "bf16_d64_rows256_c14": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, head_dim=64, window=64, seqlens=(2100,),
+                                  chunk=14, n_spans=(8,)),
+    "bf16_d64_rows512_c8": small("llama8b_8k", n_q_heads=16, n_kv_heads=2, head_dim=64, window=64, seqlens=(900,),
+                                 chunk=8, n_spans=(4,)),
+    "bf16_rows128_c64": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(1300,), chunk=64, n_spans=(5,)),
+    "bf16_rows128_c40": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(1111,), chunk=40, n_spans=(5,)),
+    "bf16_rows256_c6": small("llama8b_128k_stack", seqlens=(3000,), chunk=6, n_spans=(12,), n_layers=1),
     "bf16_chunk1": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(515,), chunk=1, n_spans=(4,)),
     "bf16_chunk_gt_tile": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(1200,), chunk=300, n_spans=(4,)),
     "bf16_P0": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(32,), n_spans=(0,)),
