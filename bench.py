@@ -39,6 +39,14 @@ def algorithmic_bytes(wl, n_keep, n_layers, reuse):
             "stack": leaders * k_read + n_layers * gather}
 
 
+def ckv_single_pass_used(kern):
+    """The single-pass path launches no chunk-sum kernel and its row reduction is far shorter than its
+    scoring kernel; the two-pass kernels take about the same time each."""
+    a = kern.get("score_stats", {}).get("ms_per_step", 0.0)
+    b = kern.get("score_colsum", {}).get("ms_per_step", 0.0)
+    return b < 0.5 * a
+
+
 def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers):
     """The oracle, as it stands, on the first n_sample_layers layers of the same inputs."""
     from oracle import chunkkv_oracle as orc
@@ -183,6 +191,18 @@ def main():
         except Exception:
             pass
     stack_gbps = ab["stack"] / (ms * 1e-3) / 1e9
+    # the scoring kernel's matrix work: 2 * Hq * w * L * d flops per scored layer (the logits; the single-pass
+    # kernel's indicator products, a quarter more, are not algorithmic and not counted)
+    score_kind = "score_stats"
+    mfma = None
+    if score_kind in kern and wl.dtype == "bf16":
+        flops = sum(2.0 * wl.n_q_heads * wl.window * L * wl.head_dim for L in wl.seqlens) * leaders
+        passes = 1 if ckv_single_pass_used(kern) else 2
+        t = kern["score_stats"]["ms_per_step"] + (kern.get("score_colsum", {"ms_per_step": 0.0})["ms_per_step"] if passes == 2 else 0.0)
+        ach = flops / (t * 1e-3) / 1e12
+        mfma = {"bound": "mfma", "kernel": "score_stats" if passes == 1 else "score_stats+score_colsum",
+                "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0,
+                "algorithmic_flops_per_step": flops}
 
     # index reuse: same stack with R = 1
     ms_r1 = None
@@ -201,12 +221,13 @@ def main():
         "roofline": roofline,
         "stack_hbm": {"algorithmic_bytes": ab["stack"], "achieved": stack_gbps, "peak": HBM_PEAK_GBPS,
                       "unit": "GB/s", "frac": stack_gbps / HBM_PEAK_GBPS},
+        "roofline_mfma": mfma,
         "kernels_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in kern.items()},
         "reuse_speedup_vs_R1": (ms_r1 / ms) if ms_r1 else None,
         "ms_per_step_R1": ms_r1,
     }
     if not args.no_cpu:
-        n_cpu = args.cpu_layers or min(N, 2 * R if wl.seqlens[0] > 65536 else 4 * R)
+        n_cpu = args.cpu_layers or min(N, 8 * R if wl.seqlens[0] > 65536 else 16 * R)
         log(f"timing the CPU oracle on {n_cpu} layers ...")
         out["cpu_baseline"] = cpu_baseline(wl, layers, n_keep, R, n_cpu)
     else:
