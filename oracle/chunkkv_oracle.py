@@ -29,6 +29,9 @@ Readings taken where the paper is silent or its listings disagree
       importance is the plain sum of its probabilities over the w window rows
       of all g query heads that share the kv-head (Algorithm 3 sums over q).
   R8  Kept tokens keep their original order; the window comes last.
+  R13 Caller-supplied row normalisation (the variant for callers that run behind
+      a fused attention kernel): the natural log-sum-exp of the scaled logits
+      over the keys the row sees, window keys up to its own position included.
 
 Pins (tests/test_oracle_pins.py): rows of the softmax sum to one; invariance to
 adding a constant vector to every key; w = g = 1 reduces to a library softmax;
@@ -37,7 +40,9 @@ grid and the ragged tail; a one-hot key gives a closed form that fixes the
 scale 1/sqrt(d) and the query-head-to-kv-head map; brute-force enumeration of
 the token order for tiny P; c = 1 reduces to a stable library argsort; uniform
 scores keep tokens [0, n_keep); nesting of kept sets; identity at n_keep = P;
-R = 1 equals per-layer compression; R >= N reuses layer 0 everywhere.
+R = 1 equals per-layer compression; R >= N reuses layer 0 everywhere; the
+log-sum-exp equals a library logsumexp over the visible logits, scores from it
+equal the plain scores, and a shift of the log-sum-exp scales them by exp(-shift).
 The paper prints no worked numeric example of this path, so parity on real
 prompts is unpinned; everything above is pinned by mathematics only.
 """
@@ -114,6 +119,55 @@ def chunk_sums(imp: np.ndarray, c: int) -> np.ndarray:
 def score(q_obs: np.ndarray, k: np.ndarray, w: int, c: int, scale: Optional[float] = None):
     """(chunk_scores [Hkv][C], token_importance [Hkv][P]) of one sequence."""
     imp = token_importance(q_obs, k, w, scale)
+    return chunk_sums(imp, c), imp
+
+
+def row_log_sum_exp(q_obs: np.ndarray, k: np.ndarray, w: int, scale: Optional[float] = None) -> np.ndarray:
+    """ln of the softmax denominator of every window row: lse[hq][i] = ln sum_{j <= P+i} exp(scale * q_i . k_j)
+    over the keys the row sees (readings R1, R2).  This is what a fused prefill attention kernel leaves
+    behind for each query row (the paper runs behind FlashAttention-2, Section 4.1 setup).
+    q_obs: [Hq][w][d], k: [Hkv][L][d].  Returns [Hq][w]."""
+    q_obs, k = widen(q_obs), widen(k)
+    Hq, Hkv = q_obs.shape[0], k.shape[0]
+    g = Hq // Hkv
+    L, d = k.shape[1], k.shape[2]
+    P = L - w
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros((Hq, w))
+    for hq in range(Hq):
+        s = (q_obs[hq] @ k[hq // g].T) * scale               # [w][L]
+        for i in range(w):
+            row = s[i, :P + i + 1]
+            m = row.max()
+            out[hq, i] = m + math.log(np.exp(row - m).sum())
+    return out
+
+
+def token_importance_from_lse(q_obs: np.ndarray, k: np.ndarray, lse: np.ndarray, w: int,
+                              scale: Optional[float] = None) -> np.ndarray:
+    """Per-kv-head token importance when the caller supplies each window row's log-sum-exp:
+    p[r, j] = exp(scale * q_r . k_j - lse_r) for the non-window keys j < P, summed over the g*w rows of the
+    group (reading R7).  With lse = row_log_sum_exp(...) this is token_importance(...).
+    q_obs: [Hq][w][d], k: [Hkv][L][d], lse: [Hq][w].  Returns [Hkv][P]."""
+    q_obs, k, lse = widen(q_obs), widen(k), np.asarray(lse, dtype=np.float64)
+    Hq, Hkv = q_obs.shape[0], k.shape[0]
+    g = Hq // Hkv
+    L, d = k.shape[1], k.shape[2]
+    P = L - w
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros((Hkv, P))
+    for hq in range(Hq):
+        s = (q_obs[hq] @ k[hq // g][:P].T) * scale           # [w][P]: every window row sees all of [0, P)
+        out[hq // g] += np.exp(s - lse[hq][:, None]).sum(axis=0)
+    return out
+
+
+def score_from_lse(q_obs: np.ndarray, k: np.ndarray, lse: np.ndarray, w: int, c: int,
+                   scale: Optional[float] = None):
+    """(chunk_scores [Hkv][C], token_importance [Hkv][P]) of one sequence from caller-supplied row log-sum-exps."""
+    imp = token_importance_from_lse(q_obs, k, lse, w, scale)
     return chunk_sums(imp, c), imp
 
 

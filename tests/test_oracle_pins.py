@@ -298,3 +298,55 @@ def test_planted_span_is_found_when_strong():
     v = r.standard_normal((Hkv, L, d))
     _, _, sel, cs = orc.compress_layer(q, k, v, w, c, 20)
     assert 7 in list(sel[0][0]) and int(np.argmax(cs[0])) == 7
+
+
+# ---------------------------------------------------------------- caller-supplied log-sum-exp (reading R13)
+def test_row_log_sum_exp_is_library_logsumexp_over_visible_keys():
+    r = rng(31)
+    Hq, Hkv, w, d, L = 6, 2, 4, 8, 27
+    g, P = 3, L - w
+    q = r.standard_normal((Hq, w, d)) * 2
+    k = r.standard_normal((Hkv, L, d)) * 2
+    lse = orc.row_log_sum_exp(q, k, w, scale=0.3)
+    for hq in range(Hq):
+        for i in range(w):
+            s = 0.3 * (k[hq // g, :P + i + 1] @ q[hq, i])
+            assert abs(lse[hq, i] - logsumexp(s)) < 1e-12
+
+
+def test_identical_keys_log_sum_exp_closed_form():
+    # all keys equal: every visible logit is s0, so lse = s0 + ln(P + i + 1)
+    w, d, L = 3, 4, 11
+    P = L - w
+    q = np.full((1, w, d), 0.5)
+    k = np.full((1, L, d), 2.0)
+    s0 = (0.5 * 2.0 * d) / math.sqrt(d)
+    lse = orc.row_log_sum_exp(q, k, w)
+    assert np.allclose(lse[0], s0 + np.log(P + np.arange(w) + 1), rtol=0, atol=1e-13)
+
+
+def test_scores_from_own_log_sum_exp_equal_plain_scores():
+    r = rng(32)
+    Hq, Hkv, w, d, L, c = 8, 2, 5, 16, 64, 7
+    q = r.standard_normal((Hq, w, d))
+    k = r.standard_normal((Hkv, L, d))
+    lse = orc.row_log_sum_exp(q, k, w)
+    cs0, imp0 = orc.score(q, k, w, c)
+    cs1, imp1 = orc.score_from_lse(q, k, lse, w, c)
+    assert np.allclose(imp1, imp0, rtol=1e-12, atol=0) and np.allclose(cs1, cs0, rtol=1e-12, atol=0)
+
+
+def test_log_sum_exp_shift_scales_one_heads_contribution():
+    # lse enters as exp(-lse): raising one query head's values by ln 2 halves exactly that head's share
+    r = rng(33)
+    Hq, Hkv, w, d, L, c = 4, 2, 3, 8, 30, 4
+    q = r.standard_normal((Hq, w, d))
+    k = r.standard_normal((Hkv, L, d))
+    lse = orc.row_log_sum_exp(q, k, w)
+    _, imp = orc.score_from_lse(q, k, lse, w, c)
+    only0 = orc.token_importance_from_lse(q[:1], k[:1], lse[:1], w)      # head 0 alone (g = 1 there)
+    lse2 = lse.copy()
+    lse2[0] += math.log(2.0)
+    _, imp2 = orc.score_from_lse(q, k, lse2, w, c)
+    assert np.allclose(imp[0] - imp2[0], 0.5 * only0[0], rtol=1e-12)
+    assert np.array_equal(imp[1], imp2[1])                                # the other kv-head is untouched
