@@ -112,6 +112,25 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
                            void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
                            int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Variants for callers that run behind a fused attention kernel and therefore already hold, for every window
+ * row, the log-sum-exp of its softmax (the paper's setup computes prefill attention with FlashAttention-2,
+ * Section 4.1): the normalisation is taken from `lse` instead of being recomputed, so K is read once and the
+ * statistics pass disappears.  p[i][j] = exp(softmax_scale * q_i . k_j - lse_i); everything after that is
+ * as in chunkkv_score / chunkkv_compress_stack.
+ *   lse   device float [B][Hq][w], natural logarithm, over the keys row i sees (j <= P + i);
+ *         chunkkv_compress_stack_lse takes a host array of n_layers device pointers (entries of layers
+ *         with l % reuse != 0 may be NULL).  Values are used as given: an lse that does not match q and k
+ *         scales that row's contribution by exp(true lse - given lse).
+ * Errors as for the plain calls; CHUNKKV_ERR_NULL for a missing lse.                                          */
+int chunkkv_score_lse(const chunkkv_problem *prob, const void *q_obs, const void *k, const float *lse,
+                      float *chunk_scores, float *token_importance, void *workspace, size_t workspace_bytes,
+                      void *stream);
+int chunkkv_compress_stack_lse(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse,
+                               const void *const *q_obs, const void *const *k, const void *const *v,
+                               const float *const *lse, void *const *k_out, void *const *v_out,
+                               int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
 /* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 caches,
  * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
  * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a

@@ -13,7 +13,9 @@ from .binding import (  # noqa: F401
     chunkkv_chunk_topk,
     chunkkv_compact,
     chunkkv_compress_stack,
+    chunkkv_compress_stack_lse,
     chunkkv_score,
+    chunkkv_score_lse,
     chunkkv_set_overlap,
     chunkkv_set_single_pass,
     chunkkv_status_string,

@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_PKG, "libchunkkv.so")
 
 F32, BF16 = 0, 1
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
-           "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_set_overlap", "chunkkv_set_single_pass",
+           "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
+           "chunkkv_set_overlap", "chunkkv_set_single_pass",
            "chunkkv_timing_begin",
            "chunkkv_timing_end")
 TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact")
@@ -139,6 +140,12 @@ def load_library(path: Optional[str] = None):
     lib.chunkkv_compress_stack.argtypes = [C.POINTER(_CProblem), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(vp),
                                            C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32p, i32p, i32p, vp,
                                            C.c_size_t, vp]
+    lib.chunkkv_score_lse.restype = C.c_int
+    lib.chunkkv_score_lse.argtypes = [C.POINTER(_CProblem), vp, vp, f32p, f32p, f32p, vp, C.c_size_t, vp]
+    lib.chunkkv_compress_stack_lse.restype = C.c_int
+    lib.chunkkv_compress_stack_lse.argtypes = [C.POINTER(_CProblem), C.c_int32, C.c_int32, C.POINTER(vp),
+                                               C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                               C.POINTER(vp), i32p, i32p, i32p, vp, C.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -202,6 +209,30 @@ def chunkkv_compress_stack(prob: Problem, reuse: int, q_obs: Sequence, k: Sequen
         _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
         "chunkkv_compress_stack")
+
+
+def chunkkv_score_lse(prob: Problem, q_obs, k, lse, chunk_scores, token_importance, workspace, stream=None) -> None:
+    cp = prob.as_c()
+    _check(load_library().chunkkv_score_lse(C.byref(cp), _ptr(q_obs), _ptr(k), _ptr(lse), _ptr(chunk_scores),
+                                            _ptr(token_importance), _ptr(workspace),
+                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                            _stream(stream)), "chunkkv_score_lse")
+
+
+def chunkkv_compress_stack_lse(prob: Problem, reuse: int, q_obs: Sequence, k: Sequence, v: Sequence, lse: Sequence,
+                               k_out: Sequence, v_out: Sequence, sel_chunk, sel_len, sel_count, workspace,
+                               stream=None) -> None:
+    n = len(k)
+    cp = prob.as_c()
+
+    def table(ts):
+        return (C.c_void_p * n)(*[None if t is None else t.data_ptr() for t in ts])
+
+    _check(load_library().chunkkv_compress_stack_lse(
+        C.byref(cp), n, reuse, table(q_obs), table(k), table(v), table(lse), table(k_out), table(v_out),
+        _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
+        "chunkkv_compress_stack_lse")
 
 
 def chunkkv_set_single_pass(enable: bool) -> None:

@@ -206,8 +206,11 @@ void fill_seq(SeqTable *t, const chunkkv_problem *p, int b0, int nb) {
 }
 
 // Scores leader layers [g0, g0+ng) (pointer tables already gathered) for all sequences.
-int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, const void *const *k, int ng,
-              int leader0, float *chunk_scores, float *token_imp, int64_t imp_pitch, char *ws, hipStream_t s) {
+// lse == nullptr: the row normalisation is computed here; otherwise lse[i] is leader i's caller-supplied
+// [B][Hq][w] array and only the importance pass runs.
+int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, const void *const *k,
+              const float *const *lse, int ng, int leader0, float *chunk_scores, float *token_imp,
+              int64_t imp_pitch, char *ws, hipStream_t s) {
   const int TK = pl.geom.tile_keys;
   for (int b0 = 0; b0 < p->batch; b0 += kMaxBatchPerLaunch) {
     const int nb = p->batch - b0 < kMaxBatchPerLaunch ? p->batch - b0 : kMaxBatchPerLaunch;
@@ -236,7 +239,15 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
       split1 = s1 > split1 ? s1 : split1;
     }
     int rc;
-    if (pl.fused_ok && g_single_pass && !token_imp) {
+    if (lse) {
+      LseArgs la;
+      memset(&la, 0, sizeof(la));
+      for (int i = 0; i < ng; ++i) la.lse[i] = lse[i];
+      la.refs = a.refs; la.leader0 = leader0; la.batch0 = b0; la.batch_total = p->batch;
+      la.n_q_heads = p->n_q_heads; la.n_kv_heads = p->n_kv_heads; la.window = p->window; la.rows_pad = pl.rows_pad;
+      { Timed t(kCombine, s); rc = launch_lse_refs(la, ng, nb, s); }
+      if (rc) return rc;
+    } else if (pl.fused_ok && g_single_pass && !token_imp) {
       // one pass over K: per-(chunk, row) sums + running maxima, merge of the range statistics, weighted row sum
       a.period_keys = pl.period_keys; a.unit_keys = pl.unit_keys; a.n_periods = pl.n_periods; a.c_pad = pl.c_pad;
       a.e_buf = (float *)(ws + pl.off_ebuf);
@@ -256,11 +267,13 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
       if (rc) return rc;
       continue;
     }
-    a.tiles_per_wg = pl.tpw0;
-    { Timed t(kStats, s); rc = launch_score_pass(0, p->dtype, p->head_dim, pl.geom, a, dim3(split0, nb * p->n_kv_heads, ng), s); }
-    if (rc) return rc;
-    { Timed t(kCombine, s); rc = launch_stats_combine(a, ng, nb, TK, s); }
-    if (rc) return rc;
+    if (!lse) {
+      a.tiles_per_wg = pl.tpw0;
+      { Timed t(kStats, s); rc = launch_score_pass(0, p->dtype, p->head_dim, pl.geom, a, dim3(split0, nb * p->n_kv_heads, ng), s); }
+      if (rc) return rc;
+      { Timed t(kCombine, s); rc = launch_stats_combine(a, ng, nb, TK, s); }
+      if (rc) return rc;
+    }
     a.tiles_per_wg = pl.tpw1;
     { Timed t(kColsum, s); rc = launch_score_pass(1, p->dtype, p->head_dim, pl.geom, a, dim3(split1, nb * p->n_kv_heads, ng), s); }
     if (rc) return rc;
@@ -351,18 +364,30 @@ size_t chunkkv_workspace_bytes(const chunkkv_problem *prob, int32_t n_layers, in
   return pl.total;
 }
 
-int chunkkv_score(const chunkkv_problem *prob, const void *q_obs, const void *k, float *chunk_scores,
-                  float *token_importance, void *workspace, size_t workspace_bytes, void *stream) {
+static int score_entry(const chunkkv_problem *prob, const void *q_obs, const void *k, const float *lse, bool with_lse,
+                       float *chunk_scores, float *token_importance, void *workspace, size_t workspace_bytes,
+                       void *stream) {
   int rc = check_problem(prob, false);
   if (rc) return rc;
-  if (!q_obs || !k || !chunk_scores) return CHUNKKV_ERR_NULL;
+  if (!q_obs || !k || !chunk_scores || (with_lse && !lse)) return CHUNKKV_ERR_NULL;
   if (misaligned(q_obs) || misaligned(k)) return CHUNKKV_ERR_SHAPE;
   Plan pl;
   rc = make_plan(prob, 1, 1, &pl);
   if (rc) return rc;
   if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
-  return run_score(prob, pl, &q_obs, &k, 1, 0, chunk_scores, token_importance,
+  return run_score(prob, pl, &q_obs, &k, with_lse ? &lse : nullptr, 1, 0, chunk_scores, token_importance,
                    (int64_t)prob->score_cap * prob->chunk, (char *)workspace, (hipStream_t)stream);
+}
+
+int chunkkv_score(const chunkkv_problem *prob, const void *q_obs, const void *k, float *chunk_scores,
+                  float *token_importance, void *workspace, size_t workspace_bytes, void *stream) {
+  return score_entry(prob, q_obs, k, nullptr, false, chunk_scores, token_importance, workspace, workspace_bytes, stream);
+}
+
+int chunkkv_score_lse(const chunkkv_problem *prob, const void *q_obs, const void *k, const float *lse,
+                      float *chunk_scores, float *token_importance, void *workspace, size_t workspace_bytes,
+                      void *stream) {
+  return score_entry(prob, q_obs, k, lse, true, chunk_scores, token_importance, workspace, workspace_bytes, stream);
 }
 
 int chunkkv_chunk_topk(const chunkkv_problem *prob, const float *chunk_scores, int32_t *sel_chunk,
@@ -385,17 +410,19 @@ int chunkkv_compact(const chunkkv_problem *prob, const void *k, const void *v, c
                      (hipStream_t)stream);
 }
 
-int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,
-                           const void *const *k, const void *const *v, void *const *k_out, void *const *v_out,
-                           int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
-                           size_t workspace_bytes, void *stream) {
+static int stack_entry(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,
+                       const void *const *k, const void *const *v, const float *const *lse, bool with_lse,
+                       void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
+                       int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream) {
   int rc = check_problem(prob, true);
   if (rc) return rc;
   if (n_layers < 1 || reuse < 1) return CHUNKKV_ERR_SHAPE;
   if (!q_obs || !k || !v || !k_out || !v_out || !sel_chunk || !sel_len || !sel_count) return CHUNKKV_ERR_NULL;
+  if (with_lse && !lse) return CHUNKKV_ERR_NULL;
   for (int l = 0; l < n_layers; ++l) {
     if (!k[l] || !v[l] || !k_out[l] || !v_out[l]) return CHUNKKV_ERR_NULL;
     if (l % reuse == 0 && !q_obs[l]) return CHUNKKV_ERR_NULL;
+    if (with_lse && l % reuse == 0 && !lse[l]) return CHUNKKV_ERR_NULL;
     if (misaligned(k[l]) || misaligned(v[l]) || misaligned(k_out[l]) || misaligned(v_out[l])) return CHUNKKV_ERR_SHAPE;
     if (l % reuse == 0 && misaligned(q_obs[l])) return CHUNKKV_ERR_SHAPE;
   }
@@ -420,8 +447,12 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
   for (int g0 = 0; g0 < pl.n_leaders; g0 += pl.batch_leaders) {
     const int ng = pl.n_leaders - g0 < pl.batch_leaders ? pl.n_leaders - g0 : pl.batch_leaders;
     const void *qs[kMaxLayersPerLaunch], *ks[kMaxLayersPerLaunch];
-    for (int i = 0; i < ng; ++i) { qs[i] = q_obs[(g0 + i) * reuse]; ks[i] = k[(g0 + i) * reuse]; }
-    rc = run_score(prob, pl, qs, ks, ng, g0, scores, nullptr, 0, ws, s);
+    const float *ls[kMaxLayersPerLaunch];
+    for (int i = 0; i < ng; ++i) {
+      qs[i] = q_obs[(g0 + i) * reuse]; ks[i] = k[(g0 + i) * reuse];
+      ls[i] = with_lse ? lse[(g0 + i) * reuse] : nullptr;
+    }
+    rc = run_score(prob, pl, qs, ks, with_lse ? ls : nullptr, ng, g0, scores, nullptr, 0, ws, s);
     if (rc) return rc;
     rc = run_topk(prob, scores, g0, ng, sel_chunk, sel_len, sel_count, sel_off, s);
     if (rc) return rc;
@@ -440,6 +471,22 @@ int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_
     if (hipStreamWaitEvent(s, ov->last_event(), 0) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
   }
   return CHUNKKV_OK;
+}
+
+int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,
+                           const void *const *k, const void *const *v, void *const *k_out, void *const *v_out,
+                           int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  return stack_entry(prob, n_layers, reuse, q_obs, k, v, nullptr, false, k_out, v_out, sel_chunk, sel_len, sel_count,
+                     workspace, workspace_bytes, stream);
+}
+
+int chunkkv_compress_stack_lse(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,
+                               const void *const *k, const void *const *v, const float *const *lse,
+                               void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
+                               int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream) {
+  return stack_entry(prob, n_layers, reuse, q_obs, k, v, lse, true, k_out, v_out, sel_chunk, sel_len, sel_count,
+                     workspace, workspace_bytes, stream);
 }
 
 int chunkkv_set_single_pass(int32_t enable) {

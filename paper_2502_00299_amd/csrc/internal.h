@@ -54,6 +54,14 @@ struct ScoreArgs {
   float *m_period;         // [problem][n_periods][rows_pad]  maximum those sums are relative to
 };
 
+// Caller-supplied row log-sum-exps -> row references of the importance pass.
+struct LseArgs {
+  const float *lse[kMaxLayersPerLaunch];  // per leader layer: [batch_total][Hq][w], natural log
+  float *refs;                            // [problem][rows_pad], log2 units
+  int32_t leader0, batch0, batch_total;
+  int32_t n_q_heads, n_kv_heads, window, rows_pad;
+};
+
 struct TopkArgs {
   SeqTable seq;
   int32_t group0;             // first selection group of this launch
@@ -106,6 +114,7 @@ int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slic
                          hipStream_t s);
 int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_score_fused(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_lse_refs(const LseArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s);
 int launch_compact(int row_bytes, const CompactArgs &a, int n_layers_slice, int batch_slice,

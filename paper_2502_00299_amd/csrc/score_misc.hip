@@ -57,6 +57,24 @@ int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slic
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
+// ref_r = lse_r * log2(e): the caller's natural-log normalisation of a window row in the importance pass's
+// units.  grid: x = (sequence, kv-head), y = leader; one thread per (padded) row.
+__global__ void lse_refs_kernel(LseArgs a) {
+  const int bl = blockIdx.x / a.n_kv_heads, h = blockIdx.x % a.n_kv_heads, z = blockIdx.y;
+  const int g = a.n_q_heads / a.n_kv_heads, w = a.window, nrows = g * w;
+  const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
+  const float *lse = pick(a.lse, z) + ((int64_t)(a.batch0 + bl) * a.n_q_heads + (int64_t)h * g) * w;
+  for (int row = threadIdx.x; row < a.rows_pad; row += blockDim.x)
+    a.refs[problem * a.rows_pad + row] = row < nrows ? lse[row] * 1.4426950408889634f : 0.f;
+}
+
+int launch_lse_refs(const LseArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s) {
+  if (n_leaders_slice <= 0 || batch_slice <= 0) return CHUNKKV_OK;
+  dim3 grid(batch_slice * a.n_kv_heads, n_leaders_slice);
+  hipLaunchKernelGGL(lse_refs_kernel, grid, dim3(a.rows_pad < 256 ? a.rows_pad : 256), 0, s, a);
+  return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
+}
+
 // Chunk sums from per-token importance, one wavefront per chunk, fixed summation order.
 // grid: x = chunk group of 4, y = (sequence, kv-head), z = leader.
 __global__ void chunk_sums_kernel(ScoreArgs a) {

@@ -116,6 +116,28 @@ def test_stack_argument_checks(lib):
     assert call(None, tab, 2) == 1
 
 
+def test_lse_argument_checks(lib):
+    # the log-sum-exp variants check what the plain calls check, plus the lse pointers (error paths only:
+    # every call returns before a launch)
+    p = good()
+    cp = p.as_c()
+    ws = pkg.chunkkv_workspace_bytes(p)
+    assert lib.chunkkv_score_lse(C.byref(cp), FAKE, FAKE, None, FAKE, None, FAKE, ws, None) == 1
+    assert lib.chunkkv_score_lse(C.byref(cp), FAKE, None, FAKE, FAKE, None, FAKE, ws, None) == 1
+    assert lib.chunkkv_score_lse(C.byref(cp), FAKE, FAKE, FAKE, FAKE, None, FAKE, ws - 1, None) == 4
+    n = 4
+    tab = (C.c_void_p * n)(*[0x1000] * n)
+    hole = (C.c_void_p * n)(0x1000, None, 0x1000, None)
+    nol = (C.c_void_p * n)(None, None, 0x1000, None)
+    ws4 = pkg.chunkkv_workspace_bytes(p, n, 2)
+    call = lambda lse, reuse, wsb=ws4: lib.chunkkv_compress_stack_lse(
+        C.byref(cp), n, reuse, tab, tab, tab, lse, tab, tab, FAKE, FAKE, FAKE, FAKE, wsb, None)
+    assert call(None, 2) == 1
+    assert call(nol, 2) == 1                       # leader layer 0 has no lse
+    assert call(hole, 1) == 1                      # every layer is a leader when R = 1
+    assert call(hole, 2, wsb=ws4 - 1) == 4         # lse of the non-leader layers may be missing
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         pkg.load_library(str(tmp_path / "nope.so"))

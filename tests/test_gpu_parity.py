@@ -286,3 +286,83 @@ def test_stack_keep_everything_is_identity(lib):
     torch.cuda.synchronize()
     for l in range(3):
         assert torch.equal(k_out[l], layers[l].k) and torch.equal(v_out[l], layers[l].v)
+
+
+# ------------------------------------------------------------------ caller-supplied log-sum-exp
+def device_lse(wl, li, shift_head=None):
+    """The caller's [B][Hq][w] log-sum-exps: the oracle's float64 values of the same stored inputs, rounded to
+    fp32 (what the GPU and the oracle's score_from_lse then both take as given)."""
+    out = np.zeros((wl.batch, wl.n_q_heads, wl.window), dtype=np.float32)
+    for b in range(wl.batch):
+        q, k, _ = H.seq_arrays(wl, li, b)
+        out[b] = orc.row_log_sum_exp(q, k, wl.window).astype(np.float32)
+    if shift_head is not None:
+        out[:, shift_head] += np.float32(np.log(2.0))
+    return out
+
+
+LSE_CASES = ["tiny_f32", "f32_rows160", "bf16_8k", "bf16_rows32", "bf16_rows224_g7", "bf16_rows256_w64",
+             "bf16_d64_rows256_c14", "bf16_rows512", "bf16_chunk_gt_tile", "bf16_P0", "bf16_P_lt_chunk"]
+
+
+@pytest.mark.parametrize("case", LSE_CASES)
+def test_score_lse_matches_oracle(lib, case):
+    wl = SCORE_CASES[case]
+    li = W.make_layer(wl, 0, DEV)
+    prob = H.make_problem(lib, wl, li)
+    B, Hk = wl.batch, wl.n_kv_heads
+    ws = workspace(lib, prob)
+    print(f"case={case} L={wl.seqlens} rows={wl.group * wl.window}", flush=True)
+    # the true normalisation, then one query head's raised by ln 2 (the library must take it as given)
+    for shift_head in (None, wl.n_q_heads - 1):
+        lse = device_lse(wl, li, shift_head)
+        cs = torch.full((B, Hk, prob.score_cap), -1.0, dtype=torch.float32, device=DEV)
+        imp = torch.full((B, Hk, prob.score_cap * wl.chunk), -1.0, dtype=torch.float32, device=DEV)
+        lib.chunkkv_score_lse(prob, li.q, li.k, torch.from_numpy(lse).to(DEV), cs, imp, ws)
+        torch.cuda.synchronize()
+        cs_h, imp_h = cs.cpu().numpy(), imp.cpu().numpy()
+        worst = 0.0
+        for b in range(B):
+            q, k, _ = H.seq_arrays(wl, li, b)
+            P = wl.seqlens[b] - wl.window
+            o_cs, o_imp = orc.score_from_lse(q, k, lse[b].astype(np.float64), wl.window, wl.chunk)
+            C = orc.n_chunks(P, wl.chunk)
+            for h in range(Hk):
+                worst = max(worst, H.rel_err(imp_h[b, h, :P], o_imp[h]), H.rel_err(cs_h[b, h, :C], o_cs[h]))
+                assert np.all(cs_h[b, h, C:] == -1.0) and np.all(imp_h[b, h, P:] == -1.0)
+        print(f"shifted head {shift_head}: max relative error {worst:.3e}")
+        assert worst <= H.REL_TOL
+
+
+def test_compress_stack_lse_matches_oracle(lib):
+    wl, R = small("llama8b_32k_stack", seqlens=(4096,), n_spans=(20,), n_layers=5), 2
+    N, B, Hk = wl.n_layers, wl.batch, wl.n_kv_heads
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    G = (N + R - 1) // R
+    sel_chunk, sel_len, sel_count = alloc_sel(prob, G)
+    k_out = [torch.zeros(prob.out_elements(), dtype=layers[0].k.dtype, device=DEV) for _ in range(N)]
+    v_out = [torch.zeros_like(k_out[0]) for _ in range(N)]
+    lses = [device_lse(wl, layers[l]) if l % R == 0 else None for l in range(N)]
+    lib.chunkkv_compress_stack_lse(prob, R, [layers[l].q if l % R == 0 else None for l in range(N)],
+                                   [x.k for x in layers], [x.v for x in layers],
+                                   [None if x is None else torch.from_numpy(x).to(DEV) for x in lses],
+                                   k_out, v_out, sel_chunk, sel_len, sel_count, workspace(lib, prob, N, R))
+    torch.cuda.synchronize()
+    n_diff = 0
+    for grp in range(G):
+        leader = grp * R
+        got = H.read_selection(prob, sel_chunk, sel_len, sel_count, grp)
+        for b in range(B):
+            q, k, _ = H.seq_arrays(wl, layers[leader], b)
+            P, nk = wl.seqlens[b] - wl.window, int(prob.n_keep[b])
+            o_cs, _ = orc.score_from_lse(q, k, lses[leader][b].astype(np.float64), wl.window, wl.chunk)
+            for h in range(Hk):
+                n_diff += H.check_selection(got[b][h], orc.chunk_topk(o_cs[h], P, wl.chunk, nk), o_cs[h], P, wl.chunk, nk)
+        for l in range(leader, min(leader + R, N)):
+            for b in range(B):
+                _, k, v = H.seq_arrays(wl, layers[l], b)
+                ok, ov = orc.compact(k, v, [s[0] for s in got[b]], [s[1] for s in got[b]], wl.window, wl.chunk)
+                assert np.array_equal(W.tensor_bits(H.out_view(prob, k_out[l], b)), ok), (l, b)
+                assert np.array_equal(W.tensor_bits(H.out_view(prob, v_out[l], b)), ov), (l, b)
+    print(f"chunks differing inside the tie band: {n_diff}")
