@@ -168,3 +168,54 @@ def test_ragged_batch_full_28_layers(lib):
     check_structure_everywhere(wl, prob, sel, 2)
     check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, 2)
     check_sampled_selections(lib, wl, layers, prob, sel, 2, [(13, int(np.argmin(wl.seqlens)), 0)])
+
+
+def test_stack_128k_with_caller_lse(lib, scoring_path):
+    """chunkkv_compress_stack_lse at the benchmark's shape (8 of the 32 layers): structure and gather everywhere,
+    sampled selections against the oracle's scores from the same log-sum-exps."""
+    if scoring_path == "two_pass":
+        pytest.skip("the log-sum-exp variant has one implementation; run once")
+    wl = W.get_workload("llama8b_128k_stack").with_(n_layers=8)
+    R, N = 2, 8
+    print("workload", wl.name, "8 layers R=2, caller-supplied log-sum-exps", flush=True)
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    # the caller's values: fp32 log-sum-exps from library ops on the device (harness-side input)
+    g, w, d, L = wl.group, wl.window, wl.head_dim, wl.seqlens[0]
+    P = L - w
+    hidden = torch.arange(L, device=DEV)[None, :] > (P + torch.arange(w, device=DEV))[:, None]
+    lses = []
+    for l in range(N):
+        if l % R:
+            lses.append(None)
+            continue
+        out = torch.empty((1, wl.n_q_heads, w), dtype=torch.float32, device=DEV)
+        for h in range(wl.n_kv_heads):
+            q = layers[l].q[0, h * g:(h + 1) * g].double().reshape(g * w, d)
+            s = (q @ layers[l].k[0, h].double().T) / d ** 0.5
+            out[0, h * g:(h + 1) * g] = torch.logsumexp(s.view(g, w, L).masked_fill(hidden[None], float("-inf")), dim=2).float()
+        lses.append(out)
+    G = N // R
+    sel_chunk = torch.zeros((G, 1, wl.n_kv_heads, prob.sel_cap), dtype=torch.int32, device=DEV)
+    sel_len = torch.zeros_like(sel_chunk)
+    sel_count = torch.zeros((G, 1, wl.n_kv_heads), dtype=torch.int32, device=DEV)
+    k_out = [torch.zeros(prob.out_elements(), dtype=wl.torch_dtype, device=DEV) for _ in range(N)]
+    v_out = [torch.zeros(prob.out_elements(), dtype=wl.torch_dtype, device=DEV) for _ in range(N)]
+    ws = torch.empty(lib.chunkkv_workspace_bytes(prob, N, R), dtype=torch.uint8, device=DEV)
+    lib.chunkkv_compress_stack_lse(prob, R, [layers[l].q if l % R == 0 else None for l in range(N)],
+                                   [x.k for x in layers], [x.v for x in layers], lses, k_out, v_out,
+                                   sel_chunk, sel_len, sel_count, ws)
+    torch.cuda.synchronize()
+    sel = (sel_chunk, sel_len, sel_count)
+    check_structure_everywhere(wl, prob, sel, R)
+    check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, R)
+    nk = int(prob.n_keep[0])
+    for (grp, h) in [(0, 2), (3, 7)]:
+        li = layers[grp * R]
+        q = W.tensor_bits(li.q[0, h * g:(h + 1) * g])
+        k = W.tensor_bits(li.k[0, h:h + 1])
+        lse = lses[grp * R][0, h * g:(h + 1) * g].double().cpu().numpy()
+        o_cs, _ = orc.score_from_lse(q, k, lse, w, wl.chunk)
+        got = H.read_selection(prob, *sel, grp)[0][h]
+        dd = H.check_selection(got, orc.chunk_topk(o_cs[0], P, wl.chunk, nk), o_cs[0], P, wl.chunk, nk)
+        print(f"group {grp} head {h}: {dd} chunks differ inside the tie band", flush=True)
