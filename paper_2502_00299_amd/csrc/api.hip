@@ -9,6 +9,7 @@ namespace {
 
 constexpr int kFusedTableLimit = 16384;  // bytes of LDS the single-pass kernel keeps for indicator fragments (2 KB per phase)
 constexpr int kTargetWorkgroups = 2048;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
+constexpr int kTargetWorkgroupsFused = 4096;  // single-pass kernel: finer ranges balance ragged batches, same speed on one long sequence
 // Key tiles (16 KB) one scoring launch set should hold.  Measured on MI355X: every extra dependent launch
 // costs ~30 us of idle GPU, more than splitting the stack into sets wins back, so one set it is.
 constexpr int64_t kTilesPerLaunch = 1 << 30;
@@ -169,7 +170,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
       if ((int64_t)pl->n_periods * pl->rows_pad * 64 >= (int64_t)1 << 32) pl->fused_ok = 0;
       for (int b = 0; b < p->batch; ++b)
         if (((int64_t)p->seqlen[b] + TK) * p->kv_stride_tok * 2 >= (int64_t)1 << 31) pl->fused_ok = 0;
-      pl->tpw_f = (int)((units * heads + kTargetWorkgroups - 1) / kTargetWorkgroups);
+      pl->tpw_f = (int)((units * heads + kTargetWorkgroupsFused - 1) / kTargetWorkgroupsFused);
       if (pl->tpw_f < 1) pl->tpw_f = 1;
       for (int b = 0; b < p->batch; ++b) {
         const int sp = ceil_div(ceil_div(p->seqlen[b], pl->unit_keys), pl->tpw_f);
