@@ -131,6 +131,34 @@ int chunkkv_compress_stack_lse(const chunkkv_problem *prob, int32_t n_layers, in
                                int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
                                size_t workspace_bytes, void *stream);
 
+/* Streaming form of Algorithm 2: one call per layer, in layer order, as prefill produces the layer's K and V
+ * (the paper compresses each layer's cache before the following attention blocks run, Section 3.1).  Layer
+ * `layer` with layer % reuse == 0 is scored and selected into selection group layer / reuse; every layer is
+ * compacted with the selection of its group, which an earlier call of the same sequence of calls has written.
+ *   q_obs            device [B][Hq][w][d]; may be NULL when layer % reuse != 0
+ *   lse              NULL, or the window rows' log-sum-exps as in chunkkv_score_lse (used when not NULL)
+ *   k, v, k_out, v_out   this layer's device buffers
+ *   sel_chunk, sel_len, sel_count   the arrays of chunkkv_compress_stack ([G][B][Hkv][sel_cap], [G][B][Hkv]);
+ *                    group layer / reuse is written (leader layers) or read (the others)
+ *   workspace        chunkkv_workspace_bytes(prob, 1, 1) bytes; nothing in it has to survive between calls
+ * Results are those of chunkkv_compress_stack over the same layers.  Errors as there.                       */
+int chunkkv_compress_layer(const chunkkv_problem *prob, int32_t layer, int32_t reuse, const void *q_obs,
+                           const float *lse, const void *k, const void *v, void *k_out, void *v_out,
+                           int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* Adjacent-group Jaccard similarity of the kept token sets, the diagnostic that motivates layer-wise index
+ * reuse (Section 3.3 and the similarity tables of Appendix B.2): for g = 0..n_groups-2
+ *   jaccard[g][b][h] = |S_g n S_{g+1}| / |S_g u S_{g+1}|,  S_g = non-window tokens kept by group g
+ * (1 when both sets are empty).  The window is left out: it is kept by every layer and would only raise
+ * every value by the same amount.
+ *   sel_chunk, sel_len, sel_count   selections of n_groups groups as written by the calls above (device)
+ *   jaccard          device float [n_groups - 1][B][Hkv]
+ * Malformed selections (counts outside [0, sel_cap], chunks not ascending) give unspecified values, never
+ * an out-of-bounds access.  n_groups < 2 is CHUNKKV_ERR_SHAPE.                                             */
+int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t *sel_chunk, const int32_t *sel_len,
+                    const int32_t *sel_count, float *jaccard, void *stream);
+
 /* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 caches,
  * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
  * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a

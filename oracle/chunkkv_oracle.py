@@ -42,7 +42,8 @@ the token order for tiny P; c = 1 reduces to a stable library argsort; uniform
 scores keep tokens [0, n_keep); nesting of kept sets; identity at n_keep = P;
 R = 1 equals per-layer compression; R >= N reuses layer 0 everywhere; the
 log-sum-exp equals a library logsumexp over the visible logits, scores from it
-equal the plain scores, and a shift of the log-sum-exp scales them by exp(-shift).
+equal the plain scores, and a shift of the log-sum-exp scales them by exp(-shift);
+the Jaccard similarity is pinned on hand-counted overlaps.
 The paper prints no worked numeric example of this path, so parity on real
 prompts is unpinned; everything above is pinned by mathematics only.
 """
@@ -196,6 +197,24 @@ def kept_token_indices(sel_chunk: np.ndarray, sel_len: np.ndarray, L: int, w: in
     parts = [np.arange(int(ch) * c, int(ch) * c + int(n)) for ch, n in zip(sel_chunk, sel_len)]
     parts.append(np.arange(P, L))
     return np.concatenate(parts).astype(np.int64)
+
+
+def kept_prefix_tokens(sel_chunk: Sequence[int], sel_len: Sequence[int], c: int) -> np.ndarray:
+    """Non-window token indices a selection keeps: the leading sel_len[e] tokens of chunk sel_chunk[e]."""
+    if len(sel_chunk) == 0:
+        return np.zeros(0, dtype=np.int64)
+    return np.concatenate([np.arange(int(ch) * c, int(ch) * c + int(ln)) for ch, ln in zip(sel_chunk, sel_len)])
+
+
+def jaccard(sel_a, sel_b, c: int) -> float:
+    """Jaccard similarity |A n B| / |A u B| of the non-window token sets two selections keep (the
+    adjacent-layer similarity of preserved indices that motivates index reuse, Section 3.3 and the tables
+    of Appendix B.2).  The window is left out (every layer keeps it).  Two empty sets are identical: 1.
+    sel_a, sel_b: (chunks, lens) pairs as chunk_topk returns them."""
+    a = kept_prefix_tokens(sel_a[0], sel_a[1], c)
+    b = kept_prefix_tokens(sel_b[0], sel_b[1], c)
+    union = np.union1d(a, b).size
+    return 1.0 if union == 0 else np.intersect1d(a, b).size / union
 
 
 def compact(k: np.ndarray, v: np.ndarray, sel_chunk: Sequence[np.ndarray], sel_len: Sequence[np.ndarray],

@@ -12,8 +12,10 @@ from .binding import (  # noqa: F401
     Problem,
     chunkkv_chunk_topk,
     chunkkv_compact,
+    chunkkv_compress_layer,
     chunkkv_compress_stack,
     chunkkv_compress_stack_lse,
+    chunkkv_jaccard,
     chunkkv_score,
     chunkkv_score_lse,
     chunkkv_set_overlap,

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libchunkkv.so")
 F32, BF16 = 0, 1
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
-           "chunkkv_set_overlap", "chunkkv_set_single_pass",
+           "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_set_overlap", "chunkkv_set_single_pass",
            "chunkkv_timing_begin",
            "chunkkv_timing_end")
 TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact")
@@ -146,6 +146,11 @@ def load_library(path: Optional[str] = None):
     lib.chunkkv_compress_stack_lse.argtypes = [C.POINTER(_CProblem), C.c_int32, C.c_int32, C.POINTER(vp),
                                                C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                                C.POINTER(vp), i32p, i32p, i32p, vp, C.c_size_t, vp]
+    lib.chunkkv_compress_layer.restype = C.c_int
+    lib.chunkkv_compress_layer.argtypes = [C.POINTER(_CProblem), C.c_int32, C.c_int32, vp, f32p, vp, vp, vp, vp,
+                                           i32p, i32p, i32p, vp, C.c_size_t, vp]
+    lib.chunkkv_jaccard.restype = C.c_int
+    lib.chunkkv_jaccard.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, i32p, i32p, f32p, vp]
     _lib = lib
     return lib
 
@@ -233,6 +238,22 @@ def chunkkv_compress_stack_lse(prob: Problem, reuse: int, q_obs: Sequence, k: Se
         _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
         "chunkkv_compress_stack_lse")
+
+
+def chunkkv_compress_layer(prob: Problem, layer: int, reuse: int, q_obs, lse, k, v, k_out, v_out, sel_chunk, sel_len,
+                           sel_count, workspace, stream=None) -> None:
+    cp = prob.as_c()
+    _check(load_library().chunkkv_compress_layer(
+        C.byref(cp), layer, reuse, _ptr(q_obs), _ptr(lse), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
+        _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
+        "chunkkv_compress_layer")
+
+
+def chunkkv_jaccard(prob: Problem, n_groups: int, sel_chunk, sel_len, sel_count, jaccard, stream=None) -> None:
+    cp = prob.as_c()
+    _check(load_library().chunkkv_jaccard(C.byref(cp), n_groups, _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count),
+                                          _ptr(jaccard), _stream(stream)), "chunkkv_jaccard")
 
 
 def chunkkv_set_single_pass(enable: bool) -> None:

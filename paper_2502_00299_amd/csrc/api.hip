@@ -490,6 +490,46 @@ int chunkkv_compress_stack_lse(const chunkkv_problem *prob, int32_t n_layers, in
                      workspace, workspace_bytes, stream);
 }
 
+int chunkkv_compress_layer(const chunkkv_problem *prob, int32_t layer, int32_t reuse, const void *q_obs,
+                           const float *lse, const void *k, const void *v, void *k_out, void *v_out,
+                           int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  int rc = check_problem(prob, true);
+  if (rc) return rc;
+  if (layer < 0 || reuse < 1) return CHUNKKV_ERR_SHAPE;
+  const bool leader = layer % reuse == 0;
+  if (!k || !v || !k_out || !v_out || !sel_chunk || !sel_len || !sel_count || (leader && !q_obs)) return CHUNKKV_ERR_NULL;
+  if (misaligned(k) || misaligned(v) || misaligned(k_out) || misaligned(v_out) || (leader && misaligned(q_obs)))
+    return CHUNKKV_ERR_SHAPE;
+  Plan pl;
+  rc = make_plan(prob, 1, 1, &pl);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
+  char *ws = (char *)workspace;
+  hipStream_t s = (hipStream_t)stream;
+  // the kernels see this layer's group as group 0 of arrays that start at the group's rows
+  const int64_t row0 = (int64_t)(layer / reuse) * prob->batch * prob->n_kv_heads;
+  int32_t *sc = sel_chunk + row0 * prob->sel_cap, *sl = sel_len + row0 * prob->sel_cap, *cnt = sel_count + row0;
+  if (leader) {
+    float *scores = (float *)(ws + pl.off_scores);
+    rc = run_score(prob, pl, &q_obs, &k, lse ? &lse : nullptr, 1, 0, scores, nullptr, 0, ws, s);
+    if (rc) return rc;
+    rc = run_topk(prob, scores, 0, 1, sc, sl, cnt, nullptr, s);
+    if (rc) return rc;
+  }
+  return run_compact(prob, 0, 1, 1, &k, &v, &k_out, &v_out, sc, sl, cnt, nullptr, s);
+}
+
+int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t *sel_chunk, const int32_t *sel_len,
+                    const int32_t *sel_count, float *jaccard, void *stream) {
+  int rc = check_problem(prob, false);
+  if (rc) return rc;
+  if (n_groups < 2) return CHUNKKV_ERR_SHAPE;
+  if (!sel_chunk || !sel_len || !sel_count || !jaccard) return CHUNKKV_ERR_NULL;
+  return launch_jaccard(sel_chunk, sel_len, sel_count, prob->sel_cap, prob->chunk, prob->batch * prob->n_kv_heads,
+                        n_groups - 1, jaccard, (hipStream_t)stream);
+}
+
 int chunkkv_set_single_pass(int32_t enable) {
   g_single_pass = enable != 0;
   return CHUNKKV_OK;

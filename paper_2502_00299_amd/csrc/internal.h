@@ -114,6 +114,8 @@ int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slic
                          hipStream_t s);
 int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_score_fused(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_jaccard(const int32_t *sel_chunk, const int32_t *sel_len, const int32_t *sel_count, int sel_cap, int chunk,
+                   int rows_per_group, int n_pairs, float *out, hipStream_t s);
 int launch_lse_refs(const LseArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s);

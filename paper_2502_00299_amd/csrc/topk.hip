@@ -167,4 +167,54 @@ int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s)
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
+// Adjacent-group Jaccard similarity of two selections of one (sequence, kv-head).  Both are ascending lists
+// of (chunk, leading tokens kept); a chunk present in both shares min(len) tokens.  One workgroup per
+// (pair of groups, sequence, kv-head): every thread takes entries of the first list and finds their chunk
+// in the second by binary search; sums are reduced in a fixed order.
+__global__ __launch_bounds__(256) void jaccard_kernel(const int32_t *sel_chunk, const int32_t *sel_len,
+                                                      const int32_t *sel_count, int sel_cap, int rows_per_group,
+                                                      float *out) {
+  const int64_t ra = (int64_t)blockIdx.y * rows_per_group + blockIdx.x, rb = ra + rows_per_group;
+  int na = sel_count[ra], nb = sel_count[rb];
+  na = na < 0 ? 0 : (na > sel_cap ? sel_cap : na);
+  nb = nb < 0 ? 0 : (nb > sel_cap ? sel_cap : nb);
+  const int32_t *ca = sel_chunk + ra * sel_cap, *la = sel_len + ra * sel_cap;
+  const int32_t *cb = sel_chunk + rb * sel_cap, *lb = sel_len + rb * sel_cap;
+  int inter = 0, size_a = 0, size_b = 0;
+  for (int i = threadIdx.x; i < na; i += 256) {
+    const int ch = ca[i], ln = la[i];
+    size_a += ln;
+    int lo = 0, hi = nb;  // first entry of b with chunk >= ch
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (cb[mid] < ch) lo = mid + 1; else hi = mid;
+    }
+    if (lo < nb && cb[lo] == ch) inter += ln < lb[lo] ? ln : lb[lo];
+  }
+  for (int i = threadIdx.x; i < nb; i += 256) size_b += lb[i];
+  __shared__ int s_red[3][4];
+  for (int o = 32; o > 0; o >>= 1) {
+    inter += __shfl_xor(inter, o); size_a += __shfl_xor(size_a, o); size_b += __shfl_xor(size_b, o);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    s_red[0][threadIdx.x >> 6] = inter; s_red[1][threadIdx.x >> 6] = size_a; s_red[2][threadIdx.x >> 6] = size_b;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int it = s_red[0][0] + s_red[0][1] + s_red[0][2] + s_red[0][3];
+    const int un = s_red[1][0] + s_red[1][1] + s_red[1][2] + s_red[1][3] +
+                   s_red[2][0] + s_red[2][1] + s_red[2][2] + s_red[2][3] - it;
+    out[ra] = un > 0 ? (float)it / (float)un : 1.0f;
+  }
+}
+
+int launch_jaccard(const int32_t *sel_chunk, const int32_t *sel_len, const int32_t *sel_count, int sel_cap, int chunk,
+                   int rows_per_group, int n_pairs, float *out, hipStream_t s) {
+  (void)chunk;
+  if (rows_per_group <= 0 || n_pairs <= 0) return CHUNKKV_OK;
+  hipLaunchKernelGGL(jaccard_kernel, dim3(rows_per_group, n_pairs), dim3(256), 0, s, sel_chunk, sel_len, sel_count,
+                     sel_cap, rows_per_group, out);
+  return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
+}
+
 }  // namespace ckv

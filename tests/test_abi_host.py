@@ -138,6 +138,23 @@ def test_lse_argument_checks(lib):
     assert call(hole, 2, wsb=ws4 - 1) == 4         # lse of the non-leader layers may be missing
 
 
+def test_layer_and_jaccard_argument_checks(lib):
+    p = good()
+    cp = p.as_c()
+    ws = pkg.chunkkv_workspace_bytes(p)
+    layer = lambda l, R, q, k=FAKE, wsb=ws: lib.chunkkv_compress_layer(
+        C.byref(cp), l, R, q, None, k, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, wsb, None)
+    assert layer(-1, 2, FAKE) == 2
+    assert layer(0, 0, FAKE) == 2
+    assert layer(0, 2, None) == 1                  # a leader layer needs its window queries
+    assert layer(2, 2, None) == 1
+    assert layer(1, 2, None, k=None) == 1
+    assert layer(1, 2, None, wsb=ws - 1) == 4      # a follower layer passes the checks up to the workspace
+    assert lib.chunkkv_jaccard(C.byref(cp), 1, FAKE, FAKE, FAKE, FAKE, None) == 2
+    assert lib.chunkkv_jaccard(C.byref(cp), 3, FAKE, None, FAKE, FAKE, None) == 1
+    assert lib.chunkkv_jaccard(C.byref(cp), 3, FAKE, FAKE, FAKE, None, None) == 1
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         pkg.load_library(str(tmp_path / "nope.so"))

@@ -366,3 +366,88 @@ def test_compress_stack_lse_matches_oracle(lib):
                 assert np.array_equal(W.tensor_bits(H.out_view(prob, k_out[l], b)), ok), (l, b)
                 assert np.array_equal(W.tensor_bits(H.out_view(prob, v_out[l], b)), ov), (l, b)
     print(f"chunks differing inside the tie band: {n_diff}")
+
+
+# ------------------------------------------------------------------ streaming per-layer call, Jaccard diagnostic
+@pytest.mark.parametrize("case,R,with_lse", [("bf16_4k_x5", 2, False), ("bf16_4k_x5", 3, True), ("ragged_x4", 1, False),
+                                             ("tiny_f32_x3", 2, False)])
+def test_compress_layer_equals_stack_call(lib, case, R, with_lse):
+    """One chunkkv_compress_layer call per layer gives bit for bit what chunkkv_compress_stack(_lse) gives
+    (which the tests above hold against the oracle)."""
+    wl, _ = STACK_CASES[case]
+    N = wl.n_layers
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    G = (N + R - 1) // R
+    qs = [layers[l].q if l % R == 0 else None for l in range(N)]
+    lses = [torch.from_numpy(device_lse(wl, layers[l])).to(DEV) if (with_lse and l % R == 0) else None for l in range(N)]
+    ref_sel = alloc_sel(prob, G)
+    ref_k = [torch.zeros(prob.out_elements(), dtype=layers[0].k.dtype, device=DEV) for _ in range(N)]
+    ref_v = [torch.zeros_like(ref_k[0]) for _ in range(N)]
+    if with_lse:
+        lib.chunkkv_compress_stack_lse(prob, R, qs, [x.k for x in layers], [x.v for x in layers], lses, ref_k, ref_v,
+                                       *ref_sel, workspace(lib, prob, N, R))
+    else:
+        lib.chunkkv_compress_stack(prob, R, qs, [x.k for x in layers], [x.v for x in layers], ref_k, ref_v,
+                                   *ref_sel, workspace(lib, prob, N, R))
+    got_sel = alloc_sel(prob, G)
+    got_k = [torch.zeros_like(ref_k[0]) for _ in range(N)]
+    got_v = [torch.zeros_like(ref_k[0]) for _ in range(N)]
+    ws = workspace(lib, prob, 1, 1)
+    for l in range(N):
+        ws.fill_(0xAB)                      # nothing in the workspace may have to survive between calls
+        lib.chunkkv_compress_layer(prob, l, R, qs[l], lses[l], layers[l].k, layers[l].v, got_k[l], got_v[l],
+                                   *got_sel, ws)
+    torch.cuda.synchronize()
+    counts = ref_sel[2].cpu().numpy()
+    assert np.array_equal(got_sel[2].cpu().numpy(), counts)
+    rc, rl, gc, gl = (t.cpu().numpy() for t in (ref_sel[0], ref_sel[1], got_sel[0], got_sel[1]))
+    for idx in np.ndindex(*counts.shape):
+        m = counts[idx]
+        assert np.array_equal(gc[idx][:m], rc[idx][:m]) and np.array_equal(gl[idx][:m], rl[idx][:m])
+    for l in range(N):
+        assert torch.equal(got_k[l], ref_k[l]) and torch.equal(got_v[l], ref_v[l]), l
+
+
+def test_jaccard_matches_oracle(lib):
+    wl = small("llama8b_32k_stack", seqlens=(4096, 1500), n_spans=(20, 8), n_layers=6, layout="nhd")
+    N, R, B, Hk = wl.n_layers, 1, wl.batch, wl.n_kv_heads
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    sel = alloc_sel(prob, N)
+    k_out = [torch.zeros(prob.out_elements(), dtype=layers[0].k.dtype, device=DEV) for _ in range(N)]
+    v_out = [torch.zeros_like(k_out[0]) for _ in range(N)]
+    lib.chunkkv_compress_stack(prob, R, [x.q for x in layers], [x.k for x in layers], [x.v for x in layers], k_out, v_out,
+                               *sel, workspace(lib, prob, N, R))
+    jac = torch.full((N - 1, B, Hk), -1.0, dtype=torch.float32, device=DEV)
+    lib.chunkkv_jaccard(prob, N, *sel, jac)
+    torch.cuda.synchronize()
+    jac_h = jac.cpu().numpy()
+    got = [H.read_selection(prob, *sel, g) for g in range(N)]
+    for g in range(N - 1):
+        for b in range(B):
+            for h in range(Hk):
+                want = orc.jaccard(got[g][b][h], got[g + 1][b][h], wl.chunk)
+                assert abs(jac_h[g, b, h] - want) <= 1e-6, (g, b, h, jac_h[g, b, h], want)
+    # the planted spans persist from layer to layer with probability 0.8, fresh noise otherwise
+    print("mean adjacent-layer Jaccard similarity:", float(jac_h.mean()))
+    # hand-made selections: identical, disjoint, partial overlap, both empty
+    sc, sl, cnt = alloc_sel(prob, 5)
+    def put(g, chunks, lens):
+        for b in range(B):
+            for h in range(Hk):
+                sc[g, b, h, :len(chunks)] = torch.tensor(chunks, dtype=torch.int32)
+                sl[g, b, h, :len(lens)] = torch.tensor(lens, dtype=torch.int32)
+                cnt[g, b, h] = len(chunks)
+    c = wl.chunk
+    put(0, [0, 2, 5], [c, c, 2]); put(1, [0, 2, 5], [c, c, 2]); put(2, [1, 3], [c, c]); put(3, [1, 4], [c, 3]); put(4, [], [])
+    jac2 = torch.full((4, B, Hk), -1.0, dtype=torch.float32, device=DEV)
+    lib.chunkkv_jaccard(prob, 5, sc, sl, cnt, jac2)
+    torch.cuda.synchronize()
+    j = jac2.cpu().numpy()
+    assert np.all(j[0] == 1.0) and np.all(j[1] == 0.0)
+    assert np.allclose(j[2], c / (2 * c + c + 3 - c), atol=1e-7) and np.all(j[3] == 0.0)
+    put(3, [], [])
+    lib.chunkkv_jaccard(prob, 5, sc, sl, cnt, jac2)
+    torch.cuda.synchronize()
+    assert np.all(jac2.cpu().numpy()[3] == 1.0)

@@ -350,3 +350,26 @@ def test_log_sum_exp_shift_scales_one_heads_contribution():
     _, imp2 = orc.score_from_lse(q, k, lse2, w, c)
     assert np.allclose(imp[0] - imp2[0], 0.5 * only0[0], rtol=1e-12)
     assert np.array_equal(imp[1], imp2[1])                                # the other kv-head is untouched
+
+
+# ---------------------------------------------------------------- adjacent-layer Jaccard similarity
+def test_jaccard_hand_counted_cases():
+    c = 4
+    a = (np.array([0, 2, 5]), np.array([4, 4, 2]))        # tokens 0-3, 8-11, 20-21      (10 tokens)
+    b = (np.array([2, 5, 7]), np.array([3, 4, 4]))        # tokens 8-10, 20-23, 28-31    (11 tokens)
+    # shared: 8, 9, 10, 20, 21 -> 5 ; union 10 + 11 - 5 = 16
+    assert orc.jaccard(a, b, c) == 5 / 16
+    assert orc.jaccard(b, a, c) == 5 / 16
+    assert orc.jaccard(a, a, c) == 1.0
+    assert orc.jaccard(a, (np.array([1, 3]), np.array([4, 4])), c) == 0.0
+    empty = (np.zeros(0, int), np.zeros(0, int))
+    assert orc.jaccard(empty, empty, c) == 1.0 and orc.jaccard(a, empty, c) == 0.0
+
+
+def test_jaccard_of_nested_selections_is_the_size_ratio():
+    # selections of the same scores with budgets n1 < n2 are nested, so J = n1 / n2
+    r = rng(41)
+    P, c = 97, 5
+    scores = r.random(orc.n_chunks(P, c))
+    s1, s2 = orc.chunk_topk(scores, P, c, 23), orc.chunk_topk(scores, P, c, 61)
+    assert abs(orc.jaccard(s1, s2, c) - 23 / 61) < 1e-15
