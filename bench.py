@@ -109,6 +109,8 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=None)
     ap.add_argument("--no-r1", action="store_true", help="skip the R=1 comparison run")
     ap.add_argument("--no-lse", action="store_true", help="skip the caller-supplied log-sum-exp leg")
+    ap.add_argument("--no-streaming", action="store_true", help="skip the per-layer streaming-call leg")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--overlap", type=int, default=0,
                     help="k > 0: score the leader layers in k sets and gather each set on a helper stream")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -250,6 +252,46 @@ def main():
         except Exception as e:  # the headline line must not depend on this leg
             log(f"log-sum-exp leg failed: {e!r}")
 
+    # the headline call replayed from a HIP graph (the call is kernels only, so a caller can capture it)
+    graph_leg = None
+    if not args.no_graph:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                run_main()
+                side.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    run_main()
+            torch.cuda.current_stream().wait_stream(side)
+            ms_g, _ = timed(graph.replay, args.steps, args.warmup)
+            graph_leg = {"ms_per_step": ms_g, "value": tokens / (ms_g * 1e-3), "unit": "prefix tokens/s"}
+            del graph
+        except Exception as e:
+            log(f"graph leg failed: {e!r}")
+
+    # the same stack through the streaming call, one chunkkv_compress_layer per layer (what a serving loop that
+    # compresses each layer right after its prefill would issue); reported beside the headline
+    stream_leg = None
+    if not args.no_streaming:
+        try:
+            G = (N + R - 1) // R
+            sc = torch.zeros((G, wl.batch, wl.n_kv_heads, prob.sel_cap), dtype=torch.int32, device=dev)
+            sl, cnt = torch.zeros_like(sc), torch.zeros((G, wl.batch, wl.n_kv_heads), dtype=torch.int32, device=dev)
+            ws_1 = torch.empty(ckv.chunkkv_workspace_bytes(prob, 1, 1), dtype=torch.uint8, device=dev)
+
+            def run_layers():
+                for l in range(N):
+                    ckv.chunkkv_compress_layer(prob, l, R, layers[l].q if l % R == 0 else None, None, ks[l], vs[l],
+                                               k_out[l], v_out[l], sc, sl, cnt, ws_1)
+            ms_s, _ = timed(run_layers, max(3, args.steps // 2), 2)
+            stream_leg = {"ms_per_step": ms_s, "value": tokens / (ms_s * 1e-3), "unit": "prefix tokens/s",
+                          "calls_per_step": N}
+            del ws_1
+        except Exception as e:
+            log(f"streaming leg failed: {e!r}")
+
     out = {
         "metric": "prefix tokens compressed/sec (32-layer stack) + achieved HBM GB/s vs peak",
         "value": value, "unit": "prefix tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -265,6 +307,8 @@ def main():
         "roofline_mfma": mfma,
         "kernels_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in kern.items()},
         "with_caller_lse": lse_leg,
+        "streaming_per_layer": stream_leg,
+        "hip_graph_replay": graph_leg,
         "reuse_speedup_vs_R1": (ms_r1 / ms) if ms_r1 else None,
         "ms_per_step_R1": ms_r1,
     }

@@ -451,3 +451,48 @@ def test_jaccard_matches_oracle(lib):
     lib.chunkkv_jaccard(prob, 5, sc, sl, cnt, jac2)
     torch.cuda.synchronize()
     assert np.all(jac2.cpu().numpy()[3] == 1.0)
+
+
+# ------------------------------------------------------------------ graph capture
+def test_stack_call_replays_from_a_hip_graph(lib):
+    """The stack call issues kernels only (no copies, memsets or allocations), so a caller can capture it;
+    every replay, with eager work and synchronisation in between, reproduces the eager result."""
+    wl = small("llama8b_32k_stack", seqlens=(4096,), n_spans=(20,), n_layers=4)
+    N, R = wl.n_layers, 2
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    G = N // R
+    qs = [layers[l].q if l % R == 0 else None for l in range(N)]
+    ks, vs = [x.k for x in layers], [x.v for x in layers]
+    ws = workspace(lib, prob, N, R)
+
+    def buffers():
+        return (alloc_sel(prob, G), [torch.zeros(prob.out_elements(), dtype=ks[0].dtype, device=DEV) for _ in range(N)],
+                [torch.zeros(prob.out_elements(), dtype=ks[0].dtype, device=DEV) for _ in range(N)])
+    e_sel, e_k, e_v = buffers()
+    lib.chunkkv_compress_stack(prob, R, qs, ks, vs, e_k, e_v, *e_sel, ws)
+    torch.cuda.synchronize()
+    g_sel, g_k, g_v = buffers()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lib.chunkkv_compress_stack(prob, R, qs, ks, vs, g_k, g_v, *g_sel, ws)   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            lib.chunkkv_compress_stack(prob, R, qs, ks, vs, g_k, g_v, *g_sel, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for t in g_k + g_v:
+            t.fill_(1.0)                      # eager work between the replays
+        g_sel[2].fill_(-3)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g_sel[2], e_sel[2]), rep
+        cnt = e_sel[2].cpu().numpy()
+        for idx in np.ndindex(*cnt.shape):
+            m = int(cnt[idx])
+            assert torch.equal(g_sel[0][idx][:m], e_sel[0][idx][:m]) and torch.equal(g_sel[1][idx][:m], e_sel[1][idx][:m])
+        for l in range(N):
+            assert torch.equal(g_k[l], e_k[l]) and torch.equal(g_v[l], e_v[l]), (rep, l)
