@@ -1,24 +1,24 @@
 // Single-pass observation-window scoring (Algorithm 1, first two steps) for bf16 caches.
 //
 // K is streamed ONCE.  The kernel is an attention forward pass whose "value" matrix is the 0/1 indicator
-// of chunk membership: for every window row r and every key block it keeps a running maximum m_r
-// (online softmax), forms e = exp2(logit*scale*log2e - m_r) and multiplies the block's e values (cast to
-// fp16, scaled by 2^12) with the indicator block on the matrix cores, so the accumulator holds, per row,
-// the sum of e over each chunk of the current PERIOD of lcm(32, c) keys (at most 16 chunk slots).
-// The accumulators are rescaled by exp2(old maximum - new maximum) every block (branch-free; the factor
-// is 1 unless the maximum grew).  At the end of a period the per-(chunk, row) sums E and the maximum
-// they are relative to are written out; the row's total sum follows from the E sums (plus the window
-// keys, which belong to no chunk).  Afterwards a merge kernel turns the per-range (max, sum) pairs into
-// ref_r = max_r + log2(sum_r) and a small reduction kernel forms
+// of chunk membership: for every window row r it keeps a reference m_r (online softmax), forms
+// e = exp2(logit*scale*log2e + 12 - m_r) for the 32 keys of a block, casts e to fp16 and multiplies it with
+// the block's indicator fragments on the matrix cores, so the accumulator holds, per row, the sum of e over
+// each chunk of the current PERIOD of lcm(32, c) keys (at most 16 chunk slots).  The reference is lazy: it
+// moves only when a block maximum exceeds it by more than kLazy, and the accumulators are rescaled only
+// then.  At the end of a period the per-(chunk, row) sums E and the reference they are relative to are
+// written out; the row's total sum follows from the E sums (plus the window keys, which belong to no
+// chunk).  Afterwards a merge kernel turns the per-range (reference, sum) pairs into
+// ref_r = m_r + log2(sum_r) and a small reduction kernel forms
 //     score[chunk] = sum_r E[chunk][r] * exp2(m_period[r] - ref_r).
 // Nothing is approximated except the fp16 rounding of e (relative 2^-11, the same values feed numerator
 // and denominator); chunk scores stay well inside the 1e-3 tolerance.
 //
-// Streaming, ring, swizzle and software pipelining are those of the two-pass kernels (score_impl.h): a
-// step issues the 16 bf16 MFMAs of block b, the LDS reads of block b+1's fragments, and block b-1's
-// exp / pack / indicator-MFMA epilogue as one scheduled region.  Every wavefront owns its 32*NQW rows
-// for all keys of the workgroup's range, so there is no cross-wavefront reduction and no barrier besides
-// the ring's.
+// Ring, swizzle and waits are those of the two-pass kernels (score_impl.h), with buffer loads as the DMA
+// instruction.  The work advances in steps (one 32-key block against one 32-row block); the body of a step
+// finishes its logits while the matrix cores compute the next step's.  Every wavefront owns its 32*NQW
+// rows for all keys of the workgroup's range, so there is no cross-wavefront reduction and no barrier
+// besides the ring's.
 #pragma once
 #include "score_impl.h"
 
