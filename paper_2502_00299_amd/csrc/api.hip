@@ -170,7 +170,14 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
       if ((int64_t)pl->n_periods * pl->rows_pad * 64 >= (int64_t)1 << 32) pl->fused_ok = 0;
       for (int b = 0; b < p->batch; ++b)
         if (((int64_t)p->seqlen[b] + TK) * p->kv_stride_tok * 2 >= (int64_t)1 << 31) pl->fused_ok = 0;
-      pl->tpw_f = (int)((units * heads + kTargetWorkgroupsFused - 1) / kTargetWorkgroupsFused);
+      // key-range length in units: at most kTargetWorkgroupsFused workgroups, and ranges of at least 8 units
+      // (40 tiles at c = 10, so that a workgroup's start-up stays small) unless that would leave fewer
+      // workgroups than the chip holds at once (512)
+      const int64_t total_units = units * heads;
+      int64_t floor_units = (total_units + 511) / 512;
+      if (floor_units > 8) floor_units = 8;
+      pl->tpw_f = (int)((total_units + kTargetWorkgroupsFused - 1) / kTargetWorkgroupsFused);
+      if (pl->tpw_f < floor_units) pl->tpw_f = (int)floor_units;
       if (pl->tpw_f < 1) pl->tpw_f = 1;
       for (int b = 0; b < p->batch; ++b) {
         const int sp = ceil_div(ceil_div(p->seqlen[b], pl->unit_keys), pl->tpw_f);
