@@ -270,6 +270,10 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
 
   // One pipeline step (see the file header).  HAS_PREV / MASKED are compile-time so that the MFMAs,
   // the fragment reads and the epilogue form one basic block the scheduler can interleave.
+  // pass 1: the accumulator start values stay in registers where the register file has room for them
+  // (bf16: every geometry; fp32 operands are twice as large), otherwise they are re-read from LDS per step
+  constexpr bool kStartInRegs = PASS == 1 && DT == CHUNKKV_BF16;
+  f32x16 start[kStartInRegs ? NQW : 1];
   u32x4 kf[NKS];
   auto step = [&](int b, f32x16 (&cur)[NQW], f32x16 (&prev)[NQW], auto has_prev_c, auto masked_c) {
     constexpr bool HAS_PREV = decltype(has_prev_c)::value;
@@ -284,10 +288,14 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
 #pragma unroll
       for (int qi = 0; qi < NQW; ++qi) {
         if constexpr (PASS == 1) {
+          if constexpr (kStartInRegs) {
+            cur[qi] = start[qi];  // becomes the C operand of the first MFMA, no copy
+          } else {
 #pragma unroll
-          for (int v4 = 0; v4 < 4; ++v4) {
-            const f32x4 st = *(const f32x4 *)(s_start + (wq * NQW + qi) * 32 + 8 * v4 + 4 * half);
-            cur[qi][4 * v4 + 0] = st.x; cur[qi][4 * v4 + 1] = st.y; cur[qi][4 * v4 + 2] = st.z; cur[qi][4 * v4 + 3] = st.w;
+            for (int v4 = 0; v4 < 4; ++v4) {
+              const f32x4 st = *(const f32x4 *)(s_start + (wq * NQW + qi) * 32 + 8 * v4 + 4 * half);
+              cur[qi][4 * v4 + 0] = st.x; cur[qi][4 * v4 + 1] = st.y; cur[qi][4 * v4 + 2] = st.z; cur[qi][4 * v4 + 3] = st.w;
+            }
           }
         } else {
 #pragma unroll
@@ -325,6 +333,15 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
   wait_tile(0);
   lds_barrier();  // every wavefront's part of tile 0 and the start values are in LDS
   if (kRing - 1 < nt) issue_tile(kRing - 1);
+  if constexpr (PASS == 1 && kStartInRegs) {
+#pragma unroll
+    for (int qi = 0; qi < NQW; ++qi)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        const f32x4 st = *(const f32x4 *)(s_start + (wq * NQW + qi) * 32 + 8 * v4 + 4 * half);
+        start[qi][4 * v4 + 0] = st.x; start[qi][4 * v4 + 1] = st.y; start[qi][4 * v4 + 2] = st.z; start[qi][4 * v4 + 3] = st.w;
+      }
+  }
   if (active) {
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) kf[ks] = *frag_ptr(0, ks);
