@@ -35,7 +35,7 @@ typedef enum {
   CHUNKKV_OK = 0,
   CHUNKKV_ERR_NULL = 1,        /* a required pointer is NULL                                     */
   CHUNKKV_ERR_SHAPE = 2,       /* inconsistent sizes: w > L, n_keep > P, Hq % Hkv != 0, caps ... */
-  CHUNKKV_ERR_UNSUPPORTED = 3, /* head_dim / dtype / row count not compiled in                   */
+  CHUNKKV_ERR_UNSUPPORTED = 3, /* head_dim / dtype / row count not compiled in, K rows span >= 2 GiB */
   CHUNKKV_ERR_WORKSPACE = 4,   /* workspace smaller than chunkkv_workspace_bytes()               */
   CHUNKKV_ERR_LAUNCH = 5       /* the HIP runtime refused a launch                               */
 } chunkkv_status;
@@ -46,7 +46,9 @@ typedef enum { CHUNKKV_F32 = 0, CHUNKKV_BF16 = 1 } chunkkv_dtype;
  * of kv-head h of sequence b starts at element  kv_base[b] + h*kv_stride_head + t*kv_stride_tok  and
  * its d elements are contiguous.  Both [B][Hkv][L][d] and packed variable-length [sum L][Hkv][d] fit.
  * Row starts must be 16-byte aligned.  Outputs use out_base / out_stride_* the same way with n_kept_b
- * tokens per head.  Supported: head_dim 64 or 128; g*w <= 512; batch, heads, L limited only by int32. */
+ * tokens per head.  Supported: head_dim 64 or 128; g*w <= 512; the K rows of one (sequence, kv-head) must
+ * span less than 2 GiB, (L_b + 256) * kv_stride_tok * element size < 2^31 (about 1 M tokens of a packed
+ * 8-head bf16 cache, 8 M tokens per head in [B][Hkv][L][d]); batch and heads limited only by int32.   */
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim;
   int32_t window, chunk;        /* w >= 1, c >= 1                                                  */

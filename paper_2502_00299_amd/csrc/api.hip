@@ -100,6 +100,9 @@ int check_problem(const chunkkv_problem *p, bool need_out) {
     const int64_t L = p->seqlen[b], nk = p->n_keep[b];
     if (L < p->window || nk < 0 || nk > L - p->window) return CHUNKKV_ERR_SHAPE;
     if (p->kv_base[b] < 0 || (p->kv_base[b] * esz) % 16) return CHUNKKV_ERR_SHAPE;
+    // the scoring kernels address the K rows of one (sequence, kv-head) through a buffer descriptor with
+    // 32-bit byte offsets (one tile of slack past the end)
+    if (((int64_t)L + 256) * p->kv_stride_tok * esz >= (int64_t)1 << 31) return CHUNKKV_ERR_UNSUPPORTED;
     if (need_out && (p->out_base[b] < 0 || (p->out_base[b] * esz) % 16)) return CHUNKKV_ERR_SHAPE;
     if (p->sel_cap < (nk + p->chunk - 1) / p->chunk + 1) return CHUNKKV_ERR_SHAPE;
     if (p->score_cap < (L - p->window + p->chunk - 1) / p->chunk) return CHUNKKV_ERR_SHAPE;
@@ -168,8 +171,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
       pl->c_pad = pl->n_periods * (int)nslots;
       // the kernels address E of one problem, and K of one (sequence, kv-head), with 32-bit byte offsets
       if ((int64_t)pl->n_periods * pl->rows_pad * 64 >= (int64_t)1 << 32) pl->fused_ok = 0;
-      for (int b = 0; b < p->batch; ++b)
-        if (((int64_t)p->seqlen[b] + TK) * p->kv_stride_tok * 2 >= (int64_t)1 << 31) pl->fused_ok = 0;
+
       // key-range length in units: at most kTargetWorkgroupsFused workgroups, and ranges of at least 8 units
       // (40 tiles at c = 10, so that a workgroup's start-up stays small) unless that would leave fewer
       // workgroups than the chip holds at once (512)

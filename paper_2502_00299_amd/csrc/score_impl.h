@@ -69,9 +69,11 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_s_barrier();
 }
 
-// DT: chunkkv_dtype, HD: head dim, NQW: 32-row blocks per wavefront, WQ: wavefronts splitting the rows
+// DT: chunkkv_dtype, HD: head dim, NQW: 32-row blocks per wavefront, WQ: wavefronts splitting the rows.
+// Two workgroups per CU, except where the operand fragments alone need more than half the register file
+// (four row blocks per wavefront; fp32 operands at head_dim 128).
 template <int DT, int HD, int NQW, int WQ, int PASS>
-__global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD == 128)) ? 1 : 2)) void score_kernel(ScoreArgs a) {
   constexpr int ESZ = DT == CHUNKKV_BF16 ? 2 : 4;
   constexpr int ROWB = HD * ESZ;
   constexpr int NSEG = ROWB / 16;
@@ -119,10 +121,12 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
   const float c1 = a.scale_log2e;
 
   // Tile i -> ring slot i % kRing.  Lane l of a 1 KB group lands at byte 16*l of the group, i.e. at
-  // (key, segment position l % NSEG); it fetches segment (position ^ key&7) of that key.  Keys past
-  // the sequence are clamped to the last row (never read out of bounds; their results are masked).
-  // The lane's byte offset inside a tile is the same for every tile (scalar tile base + 32-bit lane
-  // offset, no per-tile vector address arithmetic); only tiles reaching past L take the clamped path.
+  // (key, segment position l % NSEG); it fetches segment (position ^ key&7) of that key.  The loads are
+  // buffer loads with an LDS destination; the descriptor covers exactly the L rows of this (sequence,
+  // kv-head), so rows past the end read as zero (their results are masked) and nothing is clamped.  The
+  // lane's byte offset inside a tile is the same for every tile: scalar tile offset + 32-bit lane offset.
+  const __amdgpu_buffer_rsrc_t krsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void *)kbase, 0, (int)((uint32_t)(L - 1) * (uint32_t)ktok + ROWB), 0x00020000);
   uint32_t lane_off[kLoadsPerWave];
 #pragma unroll
   for (int j = 0; j < kLoadsPerWave; ++j) {
@@ -130,27 +134,12 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_kernel(Sco
     lane_off[j] = (uint32_t)(key * (int)ktok + ((segp ^ (key & 7)) * 16));
   }
   auto issue_tile = [&](int i) __attribute__((always_inline)) {
-    const int fk0 = tile_key0(i);
+    const uint32_t tile_off = (uint32_t)tile_key0(i) * (uint32_t)ktok;  // wavefront-uniform
     char *slot = smem + (i % kRing) * kTileBytes;
-    if (fk0 + TK <= L) {
-      const char *tbase = kbase + (int64_t)fk0 * ktok;  // wavefront-uniform
 #pragma unroll
-      for (int j = 0; j < kLoadsPerWave; ++j)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(tbase + lane_off[j]),
-                                         (__attribute__((address_space(3))) void *)(slot + (wave * kLoadsPerWave + j) * 1024),
-                                         16, 0, 0);
-    } else {
-#pragma unroll
-      for (int j = 0; j < kLoadsPerWave; ++j) {
-        const int grp = wave * kLoadsPerWave + j;
-        const int key = grp * (1024 / ROWB) + lane / NSEG, segp = lane % NSEG;
-        int gk = fk0 + key;
-        gk = gk < L ? gk : L - 1;
-        const char *src = kbase + (int64_t)gk * ktok + ((segp ^ (key & 7)) * 16);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(slot + grp * 1024), 16, 0, 0);
-      }
-    }
+    for (int j = 0; j < kLoadsPerWave; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void *)(slot + (wave * kLoadsPerWave + j) * 1024),
+                                               16, lane_off[j], tile_off, 0, 0);
   };
   // tile i has landed once at most min(2, tiles issued after it) newer tile loads are outstanding
   auto wait_tile = [&](int i) __attribute__((always_inline)) {
