@@ -76,6 +76,8 @@ def test_workspace_size_is_positive_and_grows_with_layers(lib):
     (dict(head_dim=96), 3),
     (dict(dtype=7), 3),
     (dict(window=64, n_q_heads=128, n_keep=[100]), 3),   # g*w = 1024 rows > 512
+    # K rows of one (sequence, kv-head) must span < 2 GiB: 1.1 M tokens of a packed 8-head bf16 cache do not
+    (dict(seqlen=[1_100_000], n_keep=[1000], kv_stride_head=128, kv_stride_tok=8 * 128), 3),
 ])
 def test_problem_validation(lib, kw, status):
     p = good(**kw)

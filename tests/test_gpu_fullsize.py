@@ -219,3 +219,28 @@ def test_stack_128k_with_caller_lse(lib, scoring_path):
         got = H.read_selection(prob, *sel, grp)[0][h]
         dd = H.check_selection(got, orc.chunk_topk(o_cs[0], P, wl.chunk, nk), o_cs[0], P, wl.chunk, nk)
         print(f"group {grp} head {h}: {dd} chunks differ inside the tie band", flush=True)
+
+
+def test_one_million_tokens_single_head(lib, scoring_path):
+    """Largest sizes: one kv-head of 1,000,003 tokens (a ragged last tile, block and chunk), 128 window rows.
+    Chunk scores against the oracle over the whole length, then selection and gather through the stack call."""
+    wl = W.get_workload("llama8b_8k").with_(n_q_heads=4, n_kv_heads=1, seqlens=(1_000_003,), n_spans=(300,), n_layers=1)
+    print("workload 1,000,003 tokens, 4 q / 1 kv head, w=32, c=10", scoring_path, flush=True)
+    li = W.make_layer(wl, 0, DEV)
+    prob = H.make_problem(lib, wl, li)
+    cs = torch.zeros((1, 1, prob.score_cap), dtype=torch.float32, device=DEV)
+    ws = torch.empty(lib.chunkkv_workspace_bytes(prob), dtype=torch.uint8, device=DEV)
+    lib.chunkkv_score(prob, li.q, li.k, cs, None, ws)
+    torch.cuda.synchronize()
+    q, k, _ = H.seq_arrays(wl, li, 0)
+    o_cs, _ = orc.score(q, k, wl.window, wl.chunk)
+    err = H.rel_err(cs[0, 0, :o_cs.shape[1]].cpu().numpy(), o_cs[0])
+    print(f"max relative score error over {o_cs.shape[1]} chunks: {err:.3e}", flush=True)
+    assert err <= H.REL_TOL
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, 1, [li])
+    check_structure_everywhere(wl, prob, sel, 1)
+    check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, 1)
+    P, nk = wl.seqlens[0] - wl.window, int(prob.n_keep[0])
+    got = H.read_selection(prob, *sel, 0)[0][0]
+    d = H.check_selection(got, orc.chunk_topk(o_cs[0], P, wl.chunk, nk), o_cs[0], P, wl.chunk, nk)
+    print(f"{d} chunks differ inside the tie band", flush=True)
