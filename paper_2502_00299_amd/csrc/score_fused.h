@@ -165,6 +165,7 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
   constexpr int M = KBT * NQW;  // steps per tile (even)
   u32x4 kf[4];
   f32x16 accs[2];
+  f16x8 ind0, ind1;
   // MFMAs ks0..ks1-1 of a step whose block sits at LDS offset off_s; off_n is the block of the step after it
   auto mfma_part = [&](f32x16 &acc, auto qi_c, auto ks0_c, auto ks1_c, uint32_t off_s, uint32_t off_n)
       __attribute__((always_inline)) {
@@ -204,10 +205,12 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
     f32x16 &acc = accs[PAR];
     constexpr int KSA = NKS >= 8 ? 2 : 1;  // MFMAs of the next step issued beside the maximum search
 
-    // indicator fragments of this key block, needed in part 2
-    const uint32_t taddr = lane_tab + tab_off;
-    const f16x8 ind0 = *(const f16x8 *)(smem + taddr);
-    const f16x8 ind1 = *(const f16x8 *)(smem + taddr + 16);
+    // indicator fragments of this key block (the same for all its row blocks), needed in part 2
+    if constexpr (QI == 0) {
+      const uint32_t taddr = lane_tab + tab_off;
+      ind0 = *(const f16x8 *)(smem + taddr);
+      ind1 = *(const f16x8 *)(smem + taddr + 16);
+    }
 
     // part 1: new running maximum of the row
     mfma_part(accs[PAR ^ 1], std::integral_constant<int, QI1>{}, std::integral_constant<int, 0>{},
