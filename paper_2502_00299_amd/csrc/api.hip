@@ -8,7 +8,7 @@ namespace ckv {
 namespace {
 
 constexpr int kFusedTableLimit = 16384;  // bytes of LDS the single-pass kernel keeps for indicator fragments (2 KB per phase)
-constexpr int kTargetWorkgroups = 2048;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
+constexpr int kTargetWorkgroups = 4096;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
 constexpr int kTargetWorkgroupsFused = 4096;  // single-pass kernel: finer ranges balance ragged batches, same speed on one long sequence
 // Key tiles (16 KB) one scoring launch set should hold.  Measured on MI355X: every extra dependent launch
 // costs ~30 us of idle GPU, more than splitting the stack into sets wins back, so one set it is.
