@@ -47,8 +47,12 @@ def ckv_single_pass_used(kern):
     return b < 0.5 * a
 
 
-def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers):
-    """The oracle, as it stands, on the first n_sample_layers layers of the same inputs."""
+def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers, gpu_sel=None):
+    """The oracle, as it stands, on the first n_sample_layers layers of the same inputs: Algorithm 2 written
+    out with its functions (score, chunk_topk on the leader layers, compact on every layer), timed as a whole.
+    gpu_sel = (sel_chunk, sel_len, sel_count) host arrays of the GPU run: its selections of the sampled leader
+    layers are then compared with the oracle's (chunks that differ, and whether all of them lie inside the
+    1e-3 relative tie band around the oracle's threshold score)."""
     from oracle import chunkkv_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -65,18 +69,40 @@ def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers):
             v = W.tensor_bits(li.seq_view(li.v, b, wl.n_kv_heads, wl.head_dim))
             per_seq.append((q, k, v))
         host.append(per_seq)
+    scores, sels = {}, {}
     t0 = time.perf_counter()
     for b in range(wl.batch):
-        orc.compress_stack([host[l][b][0] for l in range(n_sample_layers)],
-                           [host[l][b][1] for l in range(n_sample_layers)],
-                           [host[l][b][2] for l in range(n_sample_layers)],
-                           wl.window, wl.chunk, n_keep[b], reuse)
+        P = wl.seqlens[b] - wl.window
+        for l in range(n_sample_layers):
+            q, k, v = host[l][b]
+            if l % reuse == 0:
+                cs, _ = orc.score(q, k, wl.window, wl.chunk)
+                scores[(l, b)] = cs
+                sels[(l, b)] = [orc.chunk_topk(cs[h], P, wl.chunk, n_keep[b]) for h in range(wl.n_kv_heads)]
+            sel = sels[((l // reuse) * reuse, b)]
+            orc.compact(k, v, [x[0] for x in sel], [x[1] for x in sel], wl.window, wl.chunk)
     dt = time.perf_counter() - t0
     est_stack = dt * wl.n_layers / n_sample_layers
-    return {"value": sum(wl.seqlens) / est_stack, "unit": "prefix tokens/s", "cores": int(threads),
-            "kind": "oracle",
-            "sample": f"layers 0..{n_sample_layers - 1} of {wl.n_layers} (all sequences and kv-heads) in "
-                      f"{dt:.1f} s, scaled by {wl.n_layers}/{n_sample_layers}"}
+    out = {"value": sum(wl.seqlens) / est_stack, "unit": "prefix tokens/s", "cores": int(threads),
+           "kind": "oracle",
+           "sample": f"layers 0..{n_sample_layers - 1} of {wl.n_layers} (all sequences and kv-heads) in "
+                     f"{dt:.1f} s, scaled by {wl.n_layers}/{n_sample_layers}"}
+    if gpu_sel is not None:
+        sel_chunk, sel_len, sel_count = gpu_sel
+        differ = outside = heads = 0
+        for (l, b), per_head in sels.items():
+            for h, (oc, ol) in enumerate(per_head):
+                m = int(sel_count[l // reuse, b, h])
+                gc = sel_chunk[l // reuse, b, h, :m]
+                cs = scores[(l, b)][h]
+                thr = float(cs[oc].min()) if len(oc) else 0.0
+                d = set(gc.tolist()) ^ set(oc.tolist())
+                differ += len(d)
+                outside += sum(1 for ch in d if abs(float(cs[ch]) - thr) > 1e-3 * thr)
+                heads += 1
+        out["selection_parity"] = {"heads_compared": heads, "chunks_differing": differ,
+                                   "outside_tie_band": outside, "tie_band": "1e-3 relative to the oracle's threshold score"}
+    return out
 
 
 def window_lse(wl, li, dev):
@@ -155,6 +181,7 @@ def main():
 
         def run():
             ckv.chunkkv_compress_stack(prob, reuse, qs, ks, vs, k_out, v_out, sel_chunk, sel_len, sel_count, ws)
+        run.selection = (sel_chunk, sel_len, sel_count)
         return run
 
     def timed(run, steps, warmup, with_kernel_timing=False):
@@ -180,6 +207,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     run_main = make_run(R)
+
+    def main_sel():
+        run_main()
+        torch.cuda.synchronize()
+        return tuple(t.cpu().numpy() for t in run_main.selection)
+
     ms, _ = timed(run_main, args.steps, args.warmup)
     # per-kernel durations: a second loop of the same steps with a HIP event pair around every launch
     # (kept out of the headline loop: the event packets add gaps between the kernels)
@@ -315,7 +348,7 @@ def main():
     if not args.no_cpu:
         n_cpu = args.cpu_layers or min(N, 8 * R if wl.seqlens[0] > 65536 else 16 * R)
         log(f"timing the CPU oracle on {n_cpu} layers ...")
-        out["cpu_baseline"] = cpu_baseline(wl, layers, n_keep, R, n_cpu)
+        out["cpu_baseline"] = cpu_baseline(wl, layers, n_keep, R, n_cpu, gpu_sel=main_sel())
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)
