@@ -30,30 +30,45 @@ int launch_score_pass(int pass, int dtype, int head_dim, const ScoreGeom &g, con
                                : launch_score_f32(pass, head_dim, g, a, grid, s);
 }
 
-// ref_r = max_r + log2(sum_r) over all key ranges of a problem.  grid: x = (sequence, kv-head), y = leader.
-__global__ void stats_combine_kernel(ScoreArgs a, int tile_keys) {
+// ref_r = max_r + log2(sum_r) over all key ranges of a problem.  Four lanes share a row: each merges a
+// quarter of the ranges in one pass ((m, l) pairs merge associatively), then the four partial pairs are
+// merged with two shuffles, always in the same order.  grid: x = (sequence, kv-head), y = leader; 256 threads.
+__global__ __launch_bounds__(256) void stats_combine_kernel(ScoreArgs a, int tile_keys) {
   const int bl = blockIdx.x / a.n_kv_heads, h = blockIdx.x % a.n_kv_heads, z = blockIdx.y;
   const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
   const int L = pick(a.seq.seqlen, bl);
   const int ntiles = (L + tile_keys - 1) / tile_keys;
   const int nsplit = (ntiles + a.tiles_per_wg - 1) / a.tiles_per_wg;
-  for (int row = threadIdx.x; row < a.rows_pad; row += blockDim.x) {
-    const float2 *ps = a.part_stats + problem * a.max_split * a.rows_pad + row;
-    float m = -1.0e30f;
-    for (int s = 0; s < nsplit; ++s) m = fmaxf(m, ps[(int64_t)s * a.rows_pad].x);
-    float l = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
+  const int part = threadIdx.x & 3;
+  for (int row0 = 0; row0 < a.rows_pad; row0 += 64) {
+    const int row = row0 + (threadIdx.x >> 2);  // rows_pad is a multiple of 32; rows past it are skipped below
+    const bool live = row < a.rows_pad;
+    const float2 *ps = a.part_stats + problem * a.max_split * a.rows_pad + (live ? row : 0);
+    float m = -1.0e30f, l = 0.f;
+    for (int s = part; s < nsplit; s += 4) {
       const float2 x = ps[(int64_t)s * a.rows_pad];
-      l += x.y * exp2f(x.x - m);
+      const float mm = fmaxf(m, x.x);
+      l = l * exp2f(m - mm) + x.y * exp2f(x.x - mm);
+      m = mm;
     }
-    a.refs[problem * a.rows_pad + row] = m + log2f(l);
+#pragma unroll
+    for (int o = 1; o < 4; o <<= 1) {
+      const float mo = __shfl_xor(m, o), lo = __shfl_xor(l, o);
+      const float mm = fmaxf(m, mo);
+      // both partners compute the same sum in the same order: lower lane's term first
+      const bool low = (part & o) == 0;
+      const float a0 = (low ? l : lo) * exp2f((low ? m : mo) - mm), a1 = (low ? lo : l) * exp2f((low ? mo : m) - mm);
+      l = a0 + a1;
+      m = mm;
+    }
+    if (live && part == 0) a.refs[problem * a.rows_pad + row] = m + log2f(l);
   }
 }
 
 int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slice, int tile_keys, hipStream_t s) {
   if (n_leaders_slice <= 0 || batch_slice <= 0) return CHUNKKV_OK;
   dim3 grid(batch_slice * a.n_kv_heads, n_leaders_slice);
-  hipLaunchKernelGGL(stats_combine_kernel, grid, dim3(a.rows_pad < 256 ? a.rows_pad : 256), 0, s, a, tile_keys);
+  hipLaunchKernelGGL(stats_combine_kernel, grid, dim3(256), 0, s, a, tile_keys);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
