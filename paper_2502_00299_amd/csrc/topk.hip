@@ -132,21 +132,44 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
 
   // ---- emit in ascending chunk order
   if (tid == 0) s_pos_trunc = 0x7FFFFFFF;
+  // A thread takes kPerThread consecutive chunks per round, so a round costs two block-wide scans for
+  // kPerThread * 1024 chunks.
+  constexpr int kPerThread = 4;
   int base_sel = 0, base_eq = 0;
-  for (int i0 = 0; i0 < C; i0 += kTopkThreads) {
-    const int i = i0 + tid;
-    uint32_t key = 0;
-    if (i < C) key = order_key(scores[i]);
-    const int is_eq = i < C && key == thr;
+  for (int i0 = 0; i0 < C; i0 += kTopkThreads * kPerThread) {
+    const int first = i0 + tid * kPerThread;
+    uint32_t key[kPerThread];
+    int is_eq[kPerThread], n_eq = 0;
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int i = first + j;
+      key[j] = i < C ? order_key(scores[i]) : 0u;
+      is_eq[j] = i < C && key[j] == thr;
+      n_eq += is_eq[j];
+    }
     int tot_eq, tot_sel;
-    const int eq_rank = base_eq + block_exscan(is_eq, s_tmp, &tot_eq);
-    const int flag = i < C && (key > thr || (is_eq && eq_rank < need));
-    const int pos = base_sel + block_exscan(flag, s_tmp, &tot_sel);
-    if (flag && pos < a.sel_cap) {
-      const bool is_trunc = is_eq && eq_rank == need - 1;
-      sel_chunk[pos] = i;
-      sel_len[pos] = is_trunc ? len_trunc : (i == C - 1 ? tail_size : c);
-      if (is_trunc) s_pos_trunc = pos;
+    int eq_rank = base_eq + block_exscan(n_eq, s_tmp, &tot_eq);
+    int flag[kPerThread], n_sel = 0;
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int i = first + j;
+      flag[j] = i < C && (key[j] > thr || (is_eq[j] && eq_rank < need));
+      // remember the rank this chunk has among the equal keys, then advance it
+      is_eq[j] = is_eq[j] ? eq_rank + 1 : 0;  // 1-based rank, 0 = not equal
+      eq_rank += is_eq[j] != 0;
+      n_sel += flag[j];
+    }
+    int pos = base_sel + block_exscan(n_sel, s_tmp, &tot_sel);
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int i = first + j;
+      if (flag[j] && pos < a.sel_cap) {
+        const bool is_trunc = is_eq[j] == need;  // the need-th equal key in index order
+        sel_chunk[pos] = i;
+        sel_len[pos] = is_trunc ? len_trunc : (i == C - 1 ? tail_size : c);
+        if (is_trunc) s_pos_trunc = pos;
+      }
+      pos += flag[j];
     }
     base_eq += tot_eq;
     base_sel += tot_sel;
