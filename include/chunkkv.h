@@ -164,7 +164,9 @@ int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t
 /* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 caches,
  * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
  * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a
- * general two-pass one.
+ * general two-pass one.  The single pass rounds each exponential to fp16 relative to its row's running
+ * reference: contributions more than 2^-36 below that reference are flushed, so chunks that hold essentially no
+ * attention mass (scores below about 1e-7 of g*w) lose relative accuracy; the two-pass kernels do not.
  * chunkkv_set_single_pass(0) forces the two-pass kernels; the default is 1 (single pass where it applies). */
 int chunkkv_set_single_pass(int32_t enable);
 
