@@ -21,7 +21,7 @@ struct Plan {
   int tpw0, tpw1, max_split0;
   int fuse_chunks;
   // single-pass path: usable for this problem?  geometry and workspace
-  int fused_ok, period_keys, unit_keys, n_periods, c_pad, tpw_f, max_split_f;
+  int fused_ok, period_keys, unit_keys, n_periods, tpw_f, max_split_f;
   size_t off_part, off_refs, off_scores, off_seloff, off_imp, off_ebuf, off_mper, total;
 };
 
@@ -155,7 +155,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
     const int64_t nslots = pk / p->chunk, phases = pk / 32;
     pl->fused_ok = p->dtype == CHUNKKV_BF16 && pl->geom.wq == 4 && nslots <= 16 &&
                    phases * 2048 <= kFusedTableLimit;
-    pl->period_keys = pl->unit_keys = pl->n_periods = pl->c_pad = 0;
+    pl->period_keys = pl->unit_keys = pl->n_periods = 0;
     pl->tpw_f = pl->max_split_f = 1;
     if (pl->fused_ok) {
       int g2 = TK, y = (int)pk;
@@ -168,7 +168,6 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
         const int np = ceil_div(p->seqlen[b], pl->period_keys);
         if (np > pl->n_periods) pl->n_periods = np;
       }
-      pl->c_pad = pl->n_periods * (int)nslots;
       // the kernels address E of one problem, and K of one (sequence, kv-head), with 32-bit byte offsets
       if ((int64_t)pl->n_periods * pl->rows_pad * 64 >= (int64_t)1 << 32) pl->fused_ok = 0;
 
@@ -259,7 +258,7 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
       if (rc) return rc;
     } else if (pl.fused_ok && g_single_pass && !token_imp) {
       // one pass over K: per-(chunk, row) sums + running maxima, merge of the range statistics, weighted row sum
-      a.period_keys = pl.period_keys; a.unit_keys = pl.unit_keys; a.n_periods = pl.n_periods; a.c_pad = pl.c_pad;
+      a.period_keys = pl.period_keys; a.unit_keys = pl.unit_keys; a.n_periods = pl.n_periods;
       a.e_buf = (float *)(ws + pl.off_ebuf);
       a.m_period = (float *)(ws + pl.off_mper);
       a.max_split = pl.max_split_f;
