@@ -169,7 +169,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
         if (np > pl->n_periods) pl->n_periods = np;
       }
       // the kernels address E of one problem, and K of one (sequence, kv-head), with 32-bit byte offsets
-      if ((int64_t)pl->n_periods * pl->rows_pad * 64 >= (int64_t)1 << 32) pl->fused_ok = 0;
+      if ((int64_t)pl->n_periods * pl->rows_pad * 48 >= (int64_t)1 << 32) pl->fused_ok = 0;
 
       // key-range length in units: at most kTargetWorkgroupsFused workgroups, and ranges of at least 8 units
       // (40 tiles at c = 10, so that a workgroup's start-up stays small) unless that would leave fewer
@@ -197,7 +197,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   if (!pl->fuse_chunks) off += align256(problems * (size_t)p->score_cap * p->chunk * sizeof(float));
   pl->off_ebuf = pl->off_mper = off;
   if (pl->fused_ok) {
-    pl->off_ebuf = off; off += align256(problems * (size_t)pl->n_periods * pl->rows_pad * 16 * sizeof(float));
+    pl->off_ebuf = off; off += align256(problems * (size_t)pl->n_periods * pl->rows_pad * 48);  // 16 slots x 3 bytes
     pl->off_mper = off; off += align256(problems * (size_t)pl->n_periods * pl->rows_pad * sizeof(float));
   }
   pl->total = off < 256 ? 256 : off;

@@ -49,7 +49,7 @@ struct ScoreArgs {
   int32_t period_keys;     // lcm(32, c): keys after which the key-block / chunk pattern repeats
   int32_t unit_keys;       // lcm(tile keys, period_keys): granule of the key-range split
   int32_t n_periods;       // pitch of m_period: max over sequences of ceil(L / period_keys)
-  float *e_buf;            // [problem][n_periods][rows_pad][16]  per-(chunk slot, row) sums of e
+  float *e_buf;            // [problem][n_periods][rows_pad] x 48 bytes: per-(chunk slot, row) sums of e, 24-bit floats
   float *m_period;         // [problem][n_periods][rows_pad]  maximum those sums are relative to
 };
 

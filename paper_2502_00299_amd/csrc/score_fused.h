@@ -33,6 +33,17 @@ constexpr int kFusedLdsBytes = kRing * kTileBytes + kFusedTableBytes;
 constexpr float kHalfShift = 12.f;      // e is scaled by 2^12 before the fp16 cast (denormals below 2^-26)
 constexpr float kLazy = 2.f;            // slack of the running reference, log2 units
 
+typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
+constexpr int kEBytesPerRow = 48;  // 16 chunk slots x 3 bytes
+
+// four non-negative finite fp32 values -> their rounded upper three bytes, packed into three dwords
+__device__ __forceinline__ u32x3 pack24(f32x4 v) {
+  const uint32_t a = __float_as_uint(v.x) + 0x80u, b = __float_as_uint(v.y) + 0x80u;
+  const uint32_t c = __float_as_uint(v.z) + 0x80u, d = __float_as_uint(v.w) + 0x80u;
+  return u32x3{__builtin_amdgcn_perm(b, a, 0x05030201u), __builtin_amdgcn_perm(c, b, 0x06050302u),
+               __builtin_amdgcn_perm(d, c, 0x07060503u)};
+}
+
 template <int HD, int NQW>
 __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kernel(ScoreArgs a) {
   constexpr int ROWB = HD * 2;
@@ -184,10 +195,10 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
   int ph = 0;                      // key block within the period
   int period = range0 / pk;        // period of the current key block
   uint32_t tab_off = 0;            // ph * kPhaseBytes
-  // E and m_period of this problem (byte offsets inside stay below 2^32: n_periods * rows_pad * 64)
-  char *e_problem = (char *)a.e_buf + (int64_t)problem * a.n_periods * a.rows_pad * 64;
+  // E and m_period of this problem (byte offsets inside stay below 2^32: n_periods * rows_pad * kEBytesPerRow)
+  char *e_problem = (char *)a.e_buf + (int64_t)problem * a.n_periods * a.rows_pad * kEBytesPerRow;
   char *m_problem = (char *)a.m_period + (int64_t)problem * a.n_periods * a.rows_pad * 4;
-  const uint32_t lane_eoff = (uint32_t)((wq * NQW * 32 + n) * 64 + half * 16);
+  const uint32_t lane_eoff = (uint32_t)((wq * NQW * 32 + n) * kEBytesPerRow + half * (kEBytesPerRow / 2));
   const uint32_t lane_moff = (uint32_t)((wq * NQW * 32 + n) * 4);
 
   // CLEAN: the step belongs to a tile whose keys are all prefix keys and that is not among the last tiles
@@ -291,18 +302,19 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
       }
     }
 
-    // part 3: at the end of a period (or of the range) write E and the maximum it is relative to.
-    // E layout [problem][period][row][16 slots]: registers 0..3 of a lane are slots 4*half + 0..3 and
-    // registers 4..7 slots 8 + 4*half + 0..3 (nslots <= 16), so a lane stores two 16-byte pieces.
+    // part 3: at the end of a period (or of the range) write E and the reference it is relative to.
+    // Registers 0..3 of a lane are slots 4*half + 0..3 and registers 4..7 slots 8 + 4*half + 0..3
+    // (nslots <= 16).  E row layout (kEBytesPerRow = 48): the 8 values of lane half 0, then those of half 1,
+    // each as the upper three bytes of its fp32 (rounded: 16 mantissa bits, relative 2^-17), 24 bytes per lane.
     if (ph == phases - 1 || (!CLEAN && b == nblk - 1)) {
       f32x4 lo = {acc2[QI][0], acc2[QI][1], acc2[QI][2], acc2[QI][3]};
       f32x4 hi = {acc2[QI][4], acc2[QI][5], acc2[QI][6], acc2[QI][7]};
       l_run[QI] += ((lo.x + lo.y) + (lo.z + lo.w)) + ((hi.x + hi.y) + (hi.z + hi.w));
       if (period < a.n_periods) {
         const uint32_t prow = (uint32_t)period * (uint32_t)a.rows_pad + (uint32_t)(QI * 32);  // wavefront-uniform
-        const uint32_t eoff = prow * 64u + lane_eoff;
-        *(f32x4 *)(e_problem + eoff) = lo;
-        *(f32x4 *)(e_problem + eoff + 32) = hi;
+        const uint32_t eoff = prow * (uint32_t)kEBytesPerRow + lane_eoff;
+        *(u32x3 *)(e_problem + eoff) = pack24(lo);
+        *(u32x3 *)(e_problem + eoff + 12) = pack24(hi);
         if (half == 0) *(float *)(m_problem + (prow * 4u + lane_moff)) = m_run[QI];
       }
       acc2[QI] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};

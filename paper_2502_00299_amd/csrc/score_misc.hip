@@ -123,15 +123,19 @@ int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, 
 
 // Single-pass path, last step: score[chunk] = sum over rows of E[chunk][row] * exp2(m_period[row] - ref[row]).
 // A workgroup of 256 threads takes kPeriodsPerGroup consecutive periods of one problem.  The E block of a
-// period is rows_pad x 16 floats, contiguous; thread t reads the 16-byte pieces t, t + 256, ... (row
-// t/4 + 64*i, chunk slots 4*(t%4)..+3), so every load instruction of a wavefront covers 1 KB.  The four
-// partial sums of a thread are reduced over the threads of equal t%4, in a fixed order.
+// period is rows_pad x 48 bytes, contiguous: per row the 8 values of lane half 0 (chunk slots 0..3, 8..11)
+// and the 8 of half 1 (slots 4..7, 12..15), each value the upper three bytes of an fp32.  Thread t reads
+// the 12-byte pieces t, t + 256, ... (row t/4 + 64*i, quarter t%4 = four consecutive slots), so a load
+// instruction of a wavefront covers 768 contiguous bytes.  The four partial sums of a thread are reduced
+// over the threads of equal t%4, in a fixed order.
 // grid: x = period group, y = (sequence, kv-head), z = leader.
 constexpr int kPeriodsPerGroup = 8;
 constexpr int kMaxRowPasses = kMaxRows / 64;
+constexpr int kEBytesPerRowMisc = 48;  // as written by the single-pass scoring kernel
 
 __global__ __launch_bounds__(256) void fused_scores_kernel(ScoreArgs a) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bl = blockIdx.y / a.n_kv_heads, h = blockIdx.y % a.n_kv_heads, z = blockIdx.z;
   const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
@@ -151,16 +155,20 @@ __global__ __launch_bounds__(256) void fused_scores_kernel(ScoreArgs a) {
     const int row = (tid >> 2) + 64 * i;
     ref[i] = (i < passes && row < nrows) ? a.refs[problem * a.rows_pad + row] : 3.0e38f;  // weight 0 for padding rows
   }
+  // first slot of the quarter this thread reads: quarters are (half 0: 0..3, 8..11), (half 1: 4..7, 12..15)
+  const int q = tid & 3, slot0 = (q & 1) * 8 + (q >> 1) * 4;
   for (int period = p0; period < p1; ++period) {
     const int64_t pr = ((int64_t)problem * a.n_periods + period) * a.rows_pad;
-    const f32x4 *src = (const f32x4 *)(a.e_buf + pr * 16);
+    const char *src = (const char *)a.e_buf + pr * kEBytesPerRowMisc;
     const float *mp = a.m_period + pr;
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < kMaxRowPasses; ++i) {
       if (i < passes) {
         const float wgt = exp2f(mp[(tid >> 2) + 64 * i] - ref[i]);
-        const f32x4 x = src[tid + 256 * i];
+        const u32x3 d = *(const u32x3 *)(src + (tid + 256 * i) * 12);
+        const f32x4 x = {__uint_as_float(d.x << 8), __uint_as_float(__builtin_amdgcn_alignbit(d.y, d.x, 24) << 8),
+                         __uint_as_float(__builtin_amdgcn_alignbit(d.z, d.y, 16) << 8), __uint_as_float(d.z & 0xFFFFFF00u)};
         v += x * wgt;
       }
     }
@@ -168,7 +176,7 @@ __global__ __launch_bounds__(256) void fused_scores_kernel(ScoreArgs a) {
     for (int o = 4; o < 64; o <<= 1) {
       v.x += __shfl_xor(v.x, o); v.y += __shfl_xor(v.y, o); v.z += __shfl_xor(v.z, o); v.w += __shfl_xor(v.w, o);
     }
-    if (lane < 4) *(f32x4 *)&s_red[period - p0][wave][4 * lane] = v;
+    if (lane < 4) *(f32x4 *)&s_red[period - p0][wave][slot0] = v;
   }
   __syncthreads();
   if (tid < kPeriodsPerGroup * 16) {
