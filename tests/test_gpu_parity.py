@@ -526,3 +526,62 @@ def test_scores_under_extreme_logit_spread(lib, scoring_path, kscale):
         for h in range(wl.n_kv_heads):
             top = np.argsort(-o_cs[h])[:C // 2]
             assert rel[h][top].max() <= H.REL_TOL
+
+
+# ------------------------------------------------------------------ seeded sweep of random shapes
+def _random_cases(n=24, seed=20250299):
+    r = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        g = int(r.choice([1, 2, 4, 7, 8]))
+        w = int(r.choice([8, 16, 32, 64]))
+        if g * w > 512:
+            continue
+        hkv = int(r.choice([1, 2, 3]))
+        d = int(r.choice([64, 128]))
+        c = int(r.choice([1, 3, 5, 8, 10, 12, 14, 20, 40, 64, 100]))
+        B = int(r.choice([1, 1, 2, 3]))
+        lens = tuple(int(w + 1 + r.integers(0, 4000)) for _ in range(B))
+        pct = int(r.choice([5, 10, 20, 35, 100]))
+        dtype = "f32" if (r.random() < 0.15 and d == 64) else "bf16"
+        cases.append(dict(n_q_heads=g * hkv, n_kv_heads=hkv, head_dim=d, window=w, chunk=c, seqlens=lens,
+                          n_spans=tuple(max(1, L // 300) for L in lens), keep_pct=pct, dtype=dtype, n_layers=2,
+                          layout="nhd" if B > 1 else str(r.choice(["hnd", "nhd"]))))
+    return cases
+
+
+@pytest.mark.parametrize("idx", range(24))
+def test_random_shapes_match_oracle(lib, idx):
+    """Scores, selection and gather of 24 seeded random geometries (row counts 8..512, both head dims, chunk
+    sizes with and without a short period, ragged batches, both layouts) against the oracle."""
+    kw = _random_cases()[idx]
+    wl = W.get_workload("llama8b_8k").with_(**kw)
+    N, R, B, Hk = 2, 2, wl.batch, wl.n_kv_heads
+    print(f"case {idx}: {kw}", flush=True)
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0])
+    cs = torch.full((B, Hk, prob.score_cap), -1.0, dtype=torch.float32, device=DEV)
+    lib.chunkkv_score(prob, layers[0].q, layers[0].k, cs, None, workspace(lib, prob))
+    sel = alloc_sel(prob, 1)
+    k_out = [torch.zeros(prob.out_elements(), dtype=layers[0].k.dtype, device=DEV) for _ in range(N)]
+    v_out = [torch.zeros_like(k_out[0]) for _ in range(N)]
+    lib.chunkkv_compress_stack(prob, R, [layers[0].q, None], [x.k for x in layers], [x.v for x in layers], k_out, v_out,
+                               *sel, workspace(lib, prob, N, R))
+    torch.cuda.synchronize()
+    cs_h = cs.cpu().numpy()
+    got = H.read_selection(prob, *sel, 0)
+    worst = 0.0
+    for b in range(B):
+        q, k, _ = H.seq_arrays(wl, layers[0], b)
+        P, nk = wl.seqlens[b] - wl.window, int(prob.n_keep[b])
+        o_cs, _ = orc.score(q, k, wl.window, wl.chunk)
+        C = orc.n_chunks(P, wl.chunk)
+        for h in range(Hk):
+            worst = max(worst, H.rel_err(cs_h[b, h, :C], o_cs[h]))
+            H.check_selection(got[b][h], orc.chunk_topk(o_cs[h], P, wl.chunk, nk), o_cs[h], P, wl.chunk, nk)
+        for l in range(N):
+            _, kl, vl = H.seq_arrays(wl, layers[l], b)
+            ok, ov = orc.compact(kl, vl, [s[0] for s in got[b]], [s[1] for s in got[b]], wl.window, wl.chunk)
+            assert np.array_equal(W.tensor_bits(H.out_view(prob, k_out[l], b)), ok), (l, b)
+            assert np.array_equal(W.tensor_bits(H.out_view(prob, v_out[l], b)), ov), (l, b)
+    assert worst <= H.REL_TOL, worst
