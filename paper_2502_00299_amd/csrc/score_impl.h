@@ -6,16 +6,21 @@
 // normalised, so the work is two passes over K:
 //   pass 0  (keys x rows orientation: a lane owns one window row)  streams K, keeps a running
 //           (max, sum) per row in registers, and writes one partial pair per row and key range;
-//   -----   a tiny kernel merges the partial pairs into ref_r = max_r + log2(sum_r);
+//   -----   a tiny kernel merges the partial pairs into ref_r = max_r + log2(sum_r) (or, when the caller
+//           supplies each row's log-sum-exp, converts that and pass 0 does not run at all);
 //   pass 1  (rows x keys orientation: a lane owns one key)  streams K again with the accumulators
-//           started at -ref_r/(scale*log2e), so p = exp2(acc*scale*log2e); p is summed over the rows in
+//           started at -ref_r/(scale*log2e) (kept in registers for bf16 caches, where they are the C
+//           operand of a block's first MFMA), so p = exp2(acc*scale*log2e); p is summed over the rows in
 //           registers, across the two lane halves by one shuffle, across wavefronts in LDS, and once
 //           per super-tile of kSuperKeys keys the per-token importance is reduced to chunk sums with a
 //           fixed-order segmented sum in LDS (super-tiles advance by a multiple of c, so no chunk
 //           straddles two of them and no atomics are needed: results are deterministic).
 //
-// K streaming: tiles of 16 KB travel HBM -> LDS directly (global_load_lds_dwordx4, no register
-// staging) into a ring of kRing slots, three or four tiles in flight per workgroup.  A wavefront
+// K streaming: tiles of 16 KB travel HBM -> LDS directly (buffer loads with an LDS destination, 16 bytes
+// per lane, no register staging; the buffer descriptor covers the rows of one sequence and kv-head, so
+// rows past the end read as zero) into a ring of kRing slots, three or four tiles in flight per workgroup.
+// Being buffer and not flat-segment instructions they leave the LDS counter's ordering exact, so the
+// compiler's waits before the operand reads name just the read that is needed.  A wavefront
 // instruction fills 1 KB of a slot in lane order, so the XOR swizzle of the 16-byte row segments by
 // key index is applied on the global-address side; the MFMA operand reads (one 16-byte segment per
 // lane, 32 keys per instruction) then hit distinct banks.  Completion is tracked with explicit
