@@ -366,7 +366,10 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
       if constexpr (IDX == M - 2) {
         // the refills of this step start to read tile T + 1
         wait_tile(1);      // tiles <= T + 2 have been issued
-        lds_barrier();     // tile T + 1 is in LDS; every wavefront is done with tile T - 1
+        // Tile T + 1 is in LDS; every wavefront is done with tile T - 1, whose fragments the MFMAs consumed
+        // a tile ago.  The LDS reads in flight are prefetches of tiles T and T + 1, so the barrier does not
+        // wait for them (a wait here would drain the fragment ring once per tile).
+        __builtin_amdgcn_s_barrier();
         issue_tile(T + 3);
       }
       body(T, toff, toff_next, idx_c, std::false_type{}, std::true_type{});
@@ -381,7 +384,7 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
       if constexpr (IDX == M - 2) {
         if (T + 1 < nt) {
           wait_tile(T + 2 < nt ? 1 : 0);
-          lds_barrier();
+          __builtin_amdgcn_s_barrier();
           if (T + 3 < nt) issue_tile(T + 3);
         }
       }
