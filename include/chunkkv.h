@@ -161,6 +161,14 @@ int chunkkv_compress_layer(const chunkkv_problem *prob, int32_t layer, int32_t r
 int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t *sel_chunk, const int32_t *sel_len,
                     const int32_t *sel_count, float *jaccard, void *stream);
 
+/* Selection mode of all subsequent calls (process-wide).  0 (default): exactly n_keep tokens are kept, the
+ * lowest-ranked selected chunk is cut to its leading tokens.  1: Algorithm 3 as printed in Appendix A.5 -
+ * k = min(floor(n_keep / c), C) chunks are kept whole and nothing is cut, so a head keeps k*c tokens, or
+ * fewer when the ragged last chunk is among them; in chunkkv_compact / chunkkv_compress_* the window then
+ * follows the kept tokens directly, rows past kept + w of an output head are left untouched, and the caller
+ * reads the kept count of a head as the sum of its sel_len entries.                                        */
+int chunkkv_set_whole_chunks(int32_t enable);
+
 /* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 caches,
  * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
  * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a

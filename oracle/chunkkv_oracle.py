@@ -29,6 +29,8 @@ Readings taken where the paper is silent or its listings disagree
       importance is the plain sum of its probabilities over the w window rows
       of all g query heads that share the kv-head (Algorithm 3 sums over q).
   R8  Kept tokens keep their original order; the window comes last.
+  R15 The whole-chunk variant (Algorithm 3 as printed): k = min(floor(n_keep/c), C)
+      chunks, none cut; the kept count then depends on the data (ragged tail).
   R13 Caller-supplied row normalisation (the variant for callers that run behind
       a fused attention kernel): the natural log-sum-exp of the scaled logits
       over the keys the row sees, window keys up to its own position included.
@@ -188,6 +190,20 @@ def chunk_topk(scores: np.ndarray, P: int, c: int, n_keep: int) -> Tuple[np.ndar
     order = np.concatenate([np.arange(i * c, min((i + 1) * c, P)) for i in rank]) if C else np.zeros(0, int)
     kept = np.sort(order[:n_keep])
     chunks, lens = np.unique(kept // c, return_counts=True)
+    return chunks.astype(np.int32), lens.astype(np.int32)
+
+
+def chunk_topk_whole(scores: np.ndarray, P: int, c: int, n_keep: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Selection of ONE (sequence, kv-head) as Algorithm 3 prints it (Appendix A.5): the
+    k = min(floor(n_keep / c), C) highest-scoring chunks are kept whole (ties to the lower index, reading
+    R6) and nothing is cut, so k*c tokens are kept, or fewer when the ragged last chunk is among them.
+    Returned as ascending (chunk index, chunk size) pairs."""
+    C = n_chunks(P, c)
+    assert scores.shape == (C,) and 0 <= n_keep <= P
+    k = min(n_keep // c, C)
+    rank = np.argsort(-scores, kind="stable")[:k]
+    chunks = np.sort(rank)
+    lens = np.minimum(c, P - chunks * c)
     return chunks.astype(np.int32), lens.astype(np.int32)
 
 

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     chunkkv_score_lse,
     chunkkv_set_overlap,
     chunkkv_set_single_pass,
+    chunkkv_set_whole_chunks,
     chunkkv_status_string,
     chunkkv_timing_begin,
     chunkkv_timing_end,

@@ -21,6 +21,7 @@ F32, BF16 = 0, 1
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
            "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_set_overlap", "chunkkv_set_single_pass",
+           "chunkkv_set_whole_chunks",
            "chunkkv_timing_begin",
            "chunkkv_timing_end")
 TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact")
@@ -261,6 +262,13 @@ def chunkkv_set_single_pass(enable: bool) -> None:
     lib.chunkkv_set_single_pass.restype = C.c_int
     lib.chunkkv_set_single_pass.argtypes = [C.c_int32]
     _check(lib.chunkkv_set_single_pass(1 if enable else 0), "chunkkv_set_single_pass")
+
+
+def chunkkv_set_whole_chunks(enable: bool) -> None:
+    lib = load_library()
+    lib.chunkkv_set_whole_chunks.restype = C.c_int
+    lib.chunkkv_set_whole_chunks.argtypes = [C.c_int32]
+    _check(lib.chunkkv_set_whole_chunks(1 if enable else 0), "chunkkv_set_whole_chunks")
 
 
 def chunkkv_set_overlap(enable: bool) -> None:

@@ -50,6 +50,7 @@ struct Timed {  // records an event pair around one launch when timing is on
 };
 
 // ---- helper stream for overlapping the gather with scoring inside chunkkv_compress_stack ----------
+bool g_whole_chunks = false;  // selection mode of all calls: exact budget (default) or whole chunks only
 int g_overlap_sets = 0;  // 0: one set, no helper stream; k > 0: k sets of leader layers, gather on the helper stream
 bool g_single_pass = true;  // use the single-pass scoring kernel where it applies
 struct Overlap {
@@ -305,6 +306,7 @@ int run_topk(const chunkkv_problem *p, const float *chunk_scores, int group0, in
     a.batch0 = b0; a.batch_total = p->batch; a.n_kv_heads = p->n_kv_heads; a.window = p->window; a.chunk = p->chunk;
     a.chunk_scores = chunk_scores; a.score_cap = p->score_cap; a.sel_cap = p->sel_cap;
     a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
+    a.whole_chunks = g_whole_chunks ? 1 : 0;
     int rc;
     { Timed t(kTopk, s); rc = launch_topk(a, n_groups, nb, s); }
     if (rc) return rc;
@@ -332,6 +334,7 @@ int run_compact(const chunkkv_problem *p, int l_begin, int n_layers, int reuse, 
       a.out_stride_head = p->out_stride_head; a.out_stride_tok = p->out_stride_tok;
       a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
       a.sel_cap = p->sel_cap;
+      a.whole_chunks = g_whole_chunks ? 1 : 0;
       int max_entries = 0;
       for (int i = 0; i < nb; ++i) {
         const int nk = a.seq.n_keep[i];
@@ -536,6 +539,11 @@ int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t
   if (!sel_chunk || !sel_len || !sel_count || !jaccard) return CHUNKKV_ERR_NULL;
   return launch_jaccard(sel_chunk, sel_len, sel_count, prob->sel_cap, prob->chunk, prob->batch * prob->n_kv_heads,
                         n_groups - 1, jaccard, (hipStream_t)stream);
+}
+
+int chunkkv_set_whole_chunks(int32_t enable) {
+  g_whole_chunks = enable != 0;
+  return CHUNKKV_OK;
 }
 
 int chunkkv_set_single_pass(int32_t enable) {

@@ -76,7 +76,14 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a) {
       const int wi = e - count;
       src_row = P + wi * c;
       len = w - wi * c < c ? w - wi * c : c;
-      dst_row = n_keep + wi * c;
+      int kept = n_keep;
+      if (a.whole_chunks) {
+        // the window follows the tokens the selection actually keeps (at most n_keep)
+        if (a.sel_off) kept = count > 0 ? a.sel_off[selrow * a.sel_cap + count - 1] + sel_len[count - 1] : 0;
+        else kept = s_off[i];  // the running sum has passed every selection entry here
+        kept = kept < 0 ? 0 : (kept > n_keep ? n_keep : kept);
+      }
+      dst_row = kept + wi * c;
     }
     const int half = len * NSEG, total = 2 * half;
     // segment u of the entry: K rows first, then V rows; lanes past the end re-read the last

@@ -69,6 +69,7 @@ struct TopkArgs {
   int32_t score_cap, sel_cap;
   int32_t *sel_chunk, *sel_len, *sel_count;
   int32_t *sel_off;           // [group][batch_total][Hkv][sel_cap] exclusive token offsets, or null
+  int32_t whole_chunks;       // 1: Algorithm 3 as printed: floor(n_keep / c) whole chunks, nothing is cut
 };
 
 struct CompactArgs {
@@ -83,6 +84,7 @@ struct CompactArgs {
   int64_t kv_stride_head, kv_stride_tok, out_stride_head, out_stride_tok;
   const int32_t *sel_chunk, *sel_len, *sel_count, *sel_off;  // sel_off may be null
   int32_t sel_cap;
+  int32_t whole_chunks;       // 1: the window follows the kept tokens directly (their count varies per head)
 };
 
 // Reads element i of a small table that travels as a kernel argument.  A chain of selects on the

@@ -57,7 +57,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
     return;
   }
   const int tail_size = P - (C - 1) * c;  // == c when there is no ragged tail
-  const int m0 = (n_keep + c - 1) / c;
+  // exact budget: ceil(n_keep / c) chunks, the lowest-ranked one cut; whole-chunk mode: floor(n_keep / c)
+  // chunks (at most C), none cut
+  const int m0 = a.whole_chunks ? (n_keep / c < C ? n_keep / c : C) : (n_keep + c - 1) / c;
+  if (m0 <= 0) {
+    if (tid == 0) a.sel_count[row] = 0;
+    return;
+  }
 
   __shared__ int s_hist[256];
   __shared__ int s_tmp[16];
@@ -121,14 +127,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
     tail_sel = tail_key > thr || (tail_key == thr && need == cnt_eq);
     total = m * c - (tail_sel ? c - tail_size : 0);
     __syncthreads();
-    if (total >= n_keep) break;
+    if (total >= n_keep || a.whole_chunks) break;
     m = m0 + 1;  // tail selected and budget short by < c tokens: exactly one more chunk is needed
   }
   // The lowest-ranked selected chunk is the need-th (index order) chunk with key == thr.  It is the
   // tail iff the tail's key == thr and the tail is selected.
   const bool trunc_is_tail = tail_sel && order_key(scores[C - 1]) == thr;
   const int size_trunc = trunc_is_tail ? tail_size : c;
-  const int len_trunc = n_keep - (total - size_trunc);
+  const int len_trunc = a.whole_chunks ? size_trunc : n_keep - (total - size_trunc);
 
   // ---- emit in ascending chunk order
   if (tid == 0) s_pos_trunc = 0x7FFFFFFF;

@@ -585,3 +585,75 @@ def test_random_shapes_match_oracle(lib, idx):
             assert np.array_equal(W.tensor_bits(H.out_view(prob, k_out[l], b)), ok), (l, b)
             assert np.array_equal(W.tensor_bits(H.out_view(prob, v_out[l], b)), ov), (l, b)
     assert worst <= H.REL_TOL, worst
+
+
+# ------------------------------------------------------------------ whole-chunk selection mode (Algorithm 3 as printed)
+@pytest.fixture
+def whole_chunks(lib):
+    lib.chunkkv_set_whole_chunks(True)
+    yield
+    lib.chunkkv_set_whole_chunks(False)
+
+
+@pytest.mark.parametrize("case", ["bf16_8k", "bf16_rows96", "bf16_P_lt_chunk", "tiny_f32"])
+def test_whole_chunk_topk_matches_oracle(lib, whole_chunks, case):
+    wl = SCORE_CASES[case]
+    li = W.make_layer(wl, 0, DEV)
+    r = np.random.default_rng(5)
+    B, Hk = wl.batch, wl.n_kv_heads
+    for trial in range(3):
+        # hand-made scores with many exact ties (both sides decide on the same fp32 values); the last trial
+        # makes the ragged tail chunk the best one
+        n_keep = [int(r.integers(0, L - wl.window + 1)) for L in wl.seqlens]
+        prob = H.make_problem(lib, wl, li, n_keep=n_keep)
+        scores = torch.zeros((B, Hk, prob.score_cap), dtype=torch.float32, device=DEV)
+        host = []
+        for b, L in enumerate(wl.seqlens):
+            C = orc.n_chunks(L - wl.window, wl.chunk)
+            s = r.integers(1, 6, (Hk, C)).astype(np.float32)
+            if trial == 2 and C:
+                s[:, -1] = 9.0
+            host.append(s)
+            scores[b, :, :C] = torch.from_numpy(s).to(DEV)
+        sel = alloc_sel(prob)
+        lib.chunkkv_chunk_topk(prob, scores, *sel)
+        torch.cuda.synchronize()
+        got = H.read_selection(prob, *sel, 0)
+        for b, L in enumerate(wl.seqlens):
+            for h in range(Hk):
+                oc, ol = orc.chunk_topk_whole(host[b][h].astype(np.float64), L - wl.window, wl.chunk, n_keep[b])
+                assert got[b][h][0].tolist() == oc.tolist() and got[b][h][1].tolist() == ol.tolist(), (trial, b, h)
+
+
+def test_whole_chunk_stack_matches_oracle(lib, whole_chunks):
+    wl = small("llama8b_32k_stack", seqlens=(4093,), n_spans=(20,), n_layers=3)   # P = 4061: ragged tail of 1
+    N, R, Hk = wl.n_layers, 2, wl.n_kv_heads
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl, layers[0], n_keep=[407])                        # 40 whole chunks, 7 tokens unused
+    sel = alloc_sel(prob, 2)
+    k_out = [torch.full((prob.out_elements(),), 7.0, dtype=layers[0].k.dtype, device=DEV) for _ in range(N)]
+    v_out = [torch.full((prob.out_elements(),), 7.0, dtype=layers[0].k.dtype, device=DEV) for _ in range(N)]
+    lib.chunkkv_compress_stack(prob, R, [layers[0].q, None, layers[2].q], [x.k for x in layers], [x.v for x in layers],
+                               k_out, v_out, *sel, workspace(lib, prob, N, R))
+    torch.cuda.synchronize()
+    P, c, w = wl.seqlens[0] - wl.window, wl.chunk, wl.window
+    for grp in range(2):
+        got = H.read_selection(prob, *sel, grp)[0]
+        q, k, _ = H.seq_arrays(wl, layers[grp * R], 0)
+        o_cs, _ = orc.score(q, k, w, c)
+        for h in range(Hk):
+            oc, ol = orc.chunk_topk_whole(o_cs[h], P, c, 407)
+            gc, gl = got[h]
+            assert len(gc) == 40 and np.all(gl == np.minimum(c, P - gc.astype(np.int64) * c))
+            thr = o_cs[h][oc].min()
+            for ch in set(gc.tolist()) ^ set(oc.tolist()):
+                assert abs(o_cs[h][ch] - thr) <= H.REL_TOL * thr
+        for l in range(grp * R, min(grp * R + R, N)):
+            _, kl, vl = H.seq_arrays(wl, layers[l], 0)
+            ko, vo = W.tensor_bits(H.out_view(prob, k_out[l], 0)), W.tensor_bits(H.out_view(prob, v_out[l], 0))
+            for h in range(Hk):
+                idx = orc.kept_token_indices(got[h][0], got[h][1], wl.seqlens[0], w, c)   # kept tokens, then the window
+                assert len(idx) == int(got[h][1].sum()) + w
+                assert np.array_equal(ko[h][:len(idx)], kl[h][idx]) and np.array_equal(vo[h][:len(idx)], vl[h][idx])
+                # rows past kept + w are untouched (still the fill value 7.0 = 0x40E0 in bf16)
+                assert np.all(ko[h][len(idx):] == 0x40E0) and np.all(vo[h][len(idx):] == 0x40E0)

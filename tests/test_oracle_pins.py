@@ -373,3 +373,37 @@ def test_jaccard_of_nested_selections_is_the_size_ratio():
     scores = r.random(orc.n_chunks(P, c))
     s1, s2 = orc.chunk_topk(scores, P, c, 23), orc.chunk_topk(scores, P, c, 61)
     assert abs(orc.jaccard(s1, s2, c) - 23 / 61) < 1e-15
+
+
+# ---------------------------------------------------------------- whole-chunk selection (Algorithm 3 as printed)
+@pytest.mark.parametrize("seed", range(6))
+def test_whole_chunk_selection_matches_brute_force(seed):
+    r = rng(50 + seed)
+    P, c = int(r.integers(5, 40)), int(r.integers(1, 7))
+    C = orc.n_chunks(P, c)
+    scores = r.integers(0, 4, C).astype(np.float64)          # many ties
+    n_keep = int(r.integers(0, P + 1))
+    chunks, lens = orc.chunk_topk_whole(scores, P, c, n_keep)
+    k = min(n_keep // c, C)
+    # brute force: the k best chunks under (score desc, index asc), found by repeated selection
+    left, best = list(range(C)), []
+    for _ in range(k):
+        j = max(left, key=lambda i: (scores[i], -i))
+        best.append(j)
+        left.remove(j)
+    assert sorted(best) == chunks.tolist()
+    assert lens.tolist() == [min(c, P - ch * c) for ch in sorted(best)]
+    assert int(lens.sum()) <= n_keep
+
+
+def test_whole_chunk_selection_equals_exact_budget_when_nothing_is_cut():
+    # n_keep a multiple of c and the ragged tail not among the best: both rules keep the same tokens
+    r = rng(57)
+    P, c, n_keep = 103, 10, 40
+    scores = r.random(orc.n_chunks(P, c))
+    scores[-1] = -1.0 + 1.0                                   # tail chunk ranks last (score 0)
+    a = orc.chunk_topk(scores, P, c, n_keep)
+    b = orc.chunk_topk_whole(scores, P, c, n_keep)
+    assert a[0].tolist() == b[0].tolist() and a[1].tolist() == b[1].tolist()
+    # a budget that is no multiple of c: the whole-chunk rule keeps floor(n_keep / c) chunks
+    assert len(orc.chunk_topk_whole(scores, P, c, 47)[0]) == 4 and int(orc.chunk_topk(scores, P, c, 47)[1].sum()) == 47
