@@ -185,11 +185,18 @@ __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD ==
       s_start[r] = (r < nrows ? -a.refs[problem * a.rows_pad + r] : kNegBig) / c1;
   }
 
-  // lane's LDS address of fragment segment ks of key block b
-  auto frag_ptr = [&](int b, int ks) __attribute__((always_inline)) {
-    const char *buf = smem + ((b / KPW) % kRing) * kTileBytes;
+  // Lane's LDS address of fragment segment ks of key block b: row n of the block, 16-byte segment
+  // (2*ks + half) ^ (n & 7).  ks and ks + 4 differ by 128 bytes, so four lane offsets serve every ks and the
+  // ring slot and the block within the tile are one wavefront-uniform term.
+  uint32_t kaddr[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) kaddr[j] = (uint32_t)((n * NSEG + (((2 * j + half) ^ (n & 7)) & (NSEG - 1))) * 16);
+  auto block_off = [&](int b) __attribute__((always_inline)) {
     const int kb = wk + (b % KPW) * WK;
-    return (const u32x4 *)(buf + ((kb * 32 + n) * NSEG + ((2 * ks + half) ^ (n & 7))) * 16);
+    return (uint32_t)(((b / KPW) % kRing) * kTileBytes + kb * 32 * ROWB);
+  };
+  auto frag_at = [&](uint32_t boff, int ks) __attribute__((always_inline)) {
+    return (const u32x4 *)(smem + (kaddr[ks % 4] + boff + (uint32_t)((ks / 4) * 128)));
   };
   // pass 0: does key block b touch keys a window row may not see (or keys past the sequence)?
   auto block_masked = [&](int b) __attribute__((always_inline)) { return PASS == 0 && tile_key0(b / KPW) + TK > P; };
@@ -279,6 +286,7 @@ __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD ==
     }
     if (active) {
       const int bn = b + 1 < nblk ? b + 1 : b;  // the last step re-reads its own block (unused)
+      const uint32_t boff_next = block_off(bn);
 #pragma unroll
       for (int qi = 0; qi < NQW; ++qi) {
         if constexpr (PASS == 1) {
@@ -303,7 +311,7 @@ __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD ==
           if constexpr (PASS == 0) mma<DT>(cur[qi], kf[ks], qf[qi][ks]);   // D[key][row]
           else mma<DT>(cur[qi], qf[qi][ks], kf[ks]);                       // D[row][key]
         }
-        kf[ks] = *frag_ptr(bn, ks);
+        kf[ks] = *frag_at(boff_next, ks);
       }
       if constexpr (HAS_PREV) epilogue(prev, b - 1, masked_c);
       if constexpr (DT == CHUNKKV_BF16 && HAS_PREV) {
@@ -338,7 +346,7 @@ __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD ==
   }
   if (active) {
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) kf[ks] = *frag_ptr(0, ks);
+    for (int ks = 0; ks < NKS; ++ks) kf[ks] = *frag_at(block_off(0), ks);
   }
   f32x16 accA[NQW], accB[NQW];
   step(0, accA, accB, std::false_type{}, std::false_type{});
