@@ -131,6 +131,8 @@ def main():
     ap.add_argument("--reuse", type=int, default=2)
     ap.add_argument("--keep-pct", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--dtype", choices=["bf16", "f16", "f32"], default=None,
+                    help="storage type of the synthetic caches (default: the workload's, bf16 for the headline)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-layers", type=int, default=None)
     ap.add_argument("--no-r1", action="store_true", help="skip the R=1 comparison run")
@@ -156,6 +158,8 @@ def main():
     wl = W.get_workload(args.workload)
     if args.keep_pct is not None:
         wl = wl.with_(keep_pct=args.keep_pct)
+    if args.dtype is not None:
+        wl = wl.with_(dtype=args.dtype)
     if args.layers is not None:
         wl = wl.with_(n_layers=args.layers)
     N, R = wl.n_layers, args.reuse
@@ -165,7 +169,7 @@ def main():
     n_keep = [W.keep_budget(L, wl.window, wl.keep_pct) for L in wl.seqlens]
     li0 = layers[0]
     prob = ckv.Problem(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
-                       ckv.F32 if wl.dtype == "f32" else ckv.BF16, list(wl.seqlens), n_keep, list(li0.kv_base),
+                       {"f32": ckv.F32, "bf16": ckv.BF16, "f16": ckv.F16}[wl.dtype], list(wl.seqlens), n_keep, list(li0.kv_base),
                        li0.kv_stride_head, li0.kv_stride_tok)
     k_out = [torch.empty(prob.out_elements(), dtype=wl.torch_dtype, device=dev) for _ in range(N)]
     v_out = [torch.empty(prob.out_elements(), dtype=wl.torch_dtype, device=dev) for _ in range(N)]
@@ -248,7 +252,7 @@ def main():
     # kernel's indicator products, a quarter more, are not algorithmic and not counted)
     score_kind = "score_stats"
     mfma = None
-    if score_kind in kern and wl.dtype == "bf16":
+    if score_kind in kern and wl.dtype in ("bf16", "f16"):
         flops = sum(2.0 * wl.n_q_heads * wl.window * L * wl.head_dim for L in wl.seqlens) * leaders
         passes = 1 if ckv_single_pass_used(kern) else 2
         t = kern["score_stats"]["ms_per_step"] + (kern.get("score_colsum", {"ms_per_step": 0.0})["ms_per_step"] if passes == 2 else 0.0)

@@ -40,7 +40,9 @@ typedef enum {
   CHUNKKV_ERR_LAUNCH = 5       /* the HIP runtime refused a launch                               */
 } chunkkv_status;
 
-typedef enum { CHUNKKV_F32 = 0, CHUNKKV_BF16 = 1 } chunkkv_dtype;
+/* Storage type of Q, K, V (and K', V').  Logits accumulate in fp32 for all three; the 16-bit types take the
+ * same kernels (the paper sizes its caches in fp16, Eq. 1). */
+typedef enum { CHUNKKV_F32 = 0, CHUNKKV_BF16 = 1, CHUNKKV_F16 = 2 } chunkkv_dtype;
 
 /* One batch of sequences sharing head geometry.  K and V of a layer live in one buffer each; token t
  * of kv-head h of sequence b starts at element  kv_base[b] + h*kv_stride_head + t*kv_stride_tok  and
@@ -83,7 +85,7 @@ size_t chunkkv_workspace_bytes(const chunkkv_problem *prob, int32_t n_layers, in
  *   k                 device, layout given by prob
  *   chunk_scores      device float [B][Hkv][score_cap]; entries [0, C_b) written
  *   token_importance  device float [B][Hkv][score_cap*c] or NULL; entries [0, P_b) written
- * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; f32 inputs in fp32.       */
+ * bf16 and fp16 inputs are multiplied on the matrix cores with fp32 accumulation; f32 inputs in fp32.       */
 int chunkkv_score(const chunkkv_problem *prob, const void *q_obs, const void *k, float *chunk_scores,
                   float *token_importance, void *workspace, size_t workspace_bytes, void *stream);
 
@@ -169,7 +171,7 @@ int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t
  * reads the kept count of a head as the sum of its sel_len entries.                                        */
 int chunkkv_set_whole_chunks(int32_t enable);
 
-/* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 caches,
+/* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 and fp16 caches,
  * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
  * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a
  * general two-pass one.  The single pass rounds each exponential to fp16 relative to its row's running

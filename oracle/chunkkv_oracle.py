@@ -58,7 +58,7 @@ import numpy as np
 
 
 def widen(x: np.ndarray) -> np.ndarray:
-    """Stored values to float64, exactly.  uint16 arrays are bf16 bit patterns."""
+    """Stored values to float64, exactly.  uint16 arrays are bf16 bit patterns; float16 and float32 arrays widen as is."""
     if x.dtype == np.uint16:
         return (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
     return x.astype(np.float64)

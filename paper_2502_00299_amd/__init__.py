@@ -5,6 +5,7 @@ include/chunkkv.h).  PyTorch only provides device memory and streams.
 """
 from .binding import (  # noqa: F401
     BF16,
+    F16,
     F32,
     LIB_PATH,
     SYMBOLS,

@@ -17,7 +17,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libchunkkv.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
            "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_set_overlap", "chunkkv_set_single_pass",

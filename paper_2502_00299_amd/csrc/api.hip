@@ -83,12 +83,12 @@ int check_problem(const chunkkv_problem *p, bool need_out) {
     return CHUNKKV_ERR_SHAPE;
   if (p->n_q_heads % p->n_kv_heads != 0) return CHUNKKV_ERR_SHAPE;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return CHUNKKV_ERR_SHAPE;
-  if (p->dtype != CHUNKKV_F32 && p->dtype != CHUNKKV_BF16) return CHUNKKV_ERR_UNSUPPORTED;
+  if (p->dtype != CHUNKKV_F32 && p->dtype != CHUNKKV_BF16 && p->dtype != CHUNKKV_F16) return CHUNKKV_ERR_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return CHUNKKV_ERR_UNSUPPORTED;
   const int64_t rows = (int64_t)(p->n_q_heads / p->n_kv_heads) * p->window;
   ScoreGeom g;
   if (rows > kMaxRows || !score_geometry(p->dtype, p->head_dim, (int)rows, &g)) return CHUNKKV_ERR_UNSUPPORTED;
-  const int esz = p->dtype == CHUNKKV_BF16 ? 2 : 4;
+  const int esz = elem_bytes(p->dtype);
   if (p->kv_stride_tok < p->head_dim || p->kv_stride_head < 0) return CHUNKKV_ERR_SHAPE;
   if ((p->kv_stride_tok * esz) % 16 || (p->kv_stride_head * esz) % 16) return CHUNKKV_ERR_SHAPE;
   if (p->kv_stride_tok * esz > (1 << 22)) return CHUNKKV_ERR_UNSUPPORTED;  // tile offsets are 32-bit
@@ -148,13 +148,13 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
     const int s = ceil_div(ceil_div(p->seqlen[b], TK), pl->tpw0);
     if (s > pl->max_split0) pl->max_split0 = s;
   }
-  // single-pass path (bf16, >= 65 window rows per kv-head, chunk pattern that fits the indicator table)
+  // single-pass path (bf16 or fp16, >= 65 window rows per kv-head, chunk pattern that fits the indicator table)
   {
     int gcd = 32, x = p->chunk;
     while (x) { const int t = gcd % x; gcd = x; x = t; }
     const int64_t pk = 32 / gcd * (int64_t)p->chunk;  // lcm(32, c)
     const int64_t nslots = pk / p->chunk, phases = pk / 32;
-    pl->fused_ok = p->dtype == CHUNKKV_BF16 && pl->geom.wq == 4 && nslots <= 16 &&
+    pl->fused_ok = p->dtype != CHUNKKV_F32 && pl->geom.wq == 4 && nslots <= 16 &&
                    phases * 2048 <= kFusedTableLimit;
     pl->period_keys = pl->unit_keys = pl->n_periods = 0;
     pl->tpw_f = pl->max_split_f = 1;
@@ -269,7 +269,7 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
         const int sp = ceil_div(ceil_div(a.seq.seqlen[i], pl.unit_keys), pl.tpw_f);
         splitf = sp > splitf ? sp : splitf;
       }
-      { Timed t(kStats, s); rc = launch_score_fused(p->head_dim, pl.geom, a, dim3(splitf, nb * p->n_kv_heads, ng), s); }
+      { Timed t(kStats, s); rc = launch_score_fused(p->dtype, p->head_dim, pl.geom, a, dim3(splitf, nb * p->n_kv_heads, ng), s); }
       if (rc) return rc;
       { Timed t(kCombine, s); rc = launch_stats_combine(a, ng, nb, pl.unit_keys, s); }
       if (rc) return rc;
@@ -317,7 +317,7 @@ int run_topk(const chunkkv_problem *p, const float *chunk_scores, int group0, in
 int run_compact(const chunkkv_problem *p, int l_begin, int n_layers, int reuse, const void *const *k, const void *const *v,
                 void *const *k_out, void *const *v_out, const int32_t *sel_chunk, const int32_t *sel_len,
                 const int32_t *sel_count, const int32_t *sel_off, hipStream_t s) {
-  const int esz = p->dtype == CHUNKKV_BF16 ? 2 : 4;
+  const int esz = elem_bytes(p->dtype);
   for (int l0 = l_begin; l0 < n_layers; l0 += kMaxLayersPerLaunch) {
     const int nl = n_layers - l0 < kMaxLayersPerLaunch ? n_layers - l0 : kMaxLayersPerLaunch;
     for (int b0 = 0; b0 < p->batch; b0 += kMaxBatchPerLaunch) {

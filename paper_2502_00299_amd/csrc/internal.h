@@ -106,6 +106,7 @@ struct ScoreGeom {
   int nqw;         // blocks held by one wavefront
   int wq;          // wavefronts splitting the rows (the other 4/wq split keys)
 };
+inline int elem_bytes(int dtype) { return dtype == CHUNKKV_F32 ? 4 : 2; }  // bf16 and fp16: 2
 bool score_geometry(int dtype, int head_dim, int rows, ScoreGeom *g);
 
 // Launchers (each checks hipGetLastError and returns a chunkkv_status).
@@ -114,7 +115,7 @@ int launch_score_pass(int pass, int dtype, int head_dim, const ScoreGeom &g, con
 int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slice, int tile_keys,
                          hipStream_t s);
 int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
-int launch_score_fused(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_score_fused(int dtype, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
 int launch_jaccard(const int32_t *sel_chunk, const int32_t *sel_len, const int32_t *sel_count, int sel_cap, int chunk,
                    int rows_per_group, int n_pairs, float *out, hipStream_t s);
 int launch_lse_refs(const LseArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);

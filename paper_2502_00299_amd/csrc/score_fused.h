@@ -1,4 +1,4 @@
-// Single-pass observation-window scoring (Algorithm 1, first two steps) for bf16 caches.
+// Single-pass observation-window scoring (Algorithm 1, first two steps) for bf16 and fp16 caches.
 //
 // K is streamed ONCE.  The kernel is an attention forward pass whose "value" matrix is the 0/1 indicator
 // of chunk membership: for every window row r it keeps a reference m_r (online softmax), forms
@@ -24,7 +24,6 @@
 
 namespace ckv {
 
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -44,15 +43,15 @@ __device__ __forceinline__ u32x3 pack24(f32x4 v) {
                __builtin_amdgcn_perm(d, c, 0x07060503u)};
 }
 
-template <int HD, int NQW>
+template <int DT, int HD, int NQW>
 __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kernel(ScoreArgs a) {
+  static_assert(is_16bit(DT), "the single-pass kernel takes bf16 or fp16 caches");
   constexpr int ROWB = HD * 2;
   constexpr int NSEG = ROWB / 16;
   constexpr int NKS = ROWB / 32;
   constexpr int TK = kTileBytes / ROWB;
   constexpr int KBT = TK / 32;
-  constexpr int DT = CHUNKKV_BF16;
-  constexpr int ESZ_BF16 = 2;
+  constexpr int ESZ = 2;
 
   extern __shared__ __align__(16) char smem[];
   char *s_tab = smem + kRing * kTileBytes;
@@ -77,8 +76,8 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
   const int nblk = (range_keys + 31) / 32;  // key blocks that hold at least one key of the sequence
 
   const char *qbase = (const char *)pick(a.q, z) + ((int64_t)(a.batch0 + bl) * a.n_q_heads + (int64_t)h * g) * w * ROWB;
-  const char *kbase = (const char *)pick(a.k, z) + (pick(a.seq.kv_base, bl) + (int64_t)h * a.kv_stride_head) * ESZ_BF16;
-  const int64_t ktok = a.kv_stride_tok * ESZ_BF16;
+  const char *kbase = (const char *)pick(a.k, z) + (pick(a.seq.kv_base, bl) + (int64_t)h * a.kv_stride_head) * ESZ;
+  const int64_t ktok = a.kv_stride_tok * ESZ;
   const float c1 = a.scale_log2e;
 
   // ---- K tiles: HBM -> LDS ring (ring, swizzle and waits as in score_impl.h).  The loads are buffer
@@ -404,10 +403,10 @@ __global__ __launch_bounds__(kThreads, (NQW >= 4 ? 1 : 2)) void score_fused_kern
   }
 }
 
-template <int HD, int NQW>
+template <int DT, int HD, int NQW>
 int launch_fused_cfg(const ScoreArgs &a, dim3 grid, hipStream_t s) {
   static bool attr_done = false;
-  auto kern = score_fused_kernel<HD, NQW>;
+  auto kern = score_fused_kernel<DT, HD, NQW>;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             kFusedLdsBytes) != hipSuccess)
@@ -417,6 +416,22 @@ int launch_fused_cfg(const ScoreArgs &a, dim3 grid, hipStream_t s) {
   const int lds_bytes = kRing * kTileBytes + a.period_keys / 32 * 2048;  // ring + indicator table
   hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds_bytes, s, a);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
+}
+
+// every compiled geometry of one storage type
+template <int DT>
+int launch_fused_dt(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s) {
+  if (g.wq != 4) return CHUNKKV_ERR_UNSUPPORTED;
+  if (head_dim == 128) {
+    if (g.nqw == 1) return launch_fused_cfg<DT, 128, 1>(a, grid, s);
+    if (g.nqw == 2) return launch_fused_cfg<DT, 128, 2>(a, grid, s);
+    if (g.nqw == 4) return launch_fused_cfg<DT, 128, 4>(a, grid, s);
+  } else if (head_dim == 64) {
+    if (g.nqw == 1) return launch_fused_cfg<DT, 64, 1>(a, grid, s);
+    if (g.nqw == 2) return launch_fused_cfg<DT, 64, 2>(a, grid, s);
+    if (g.nqw == 4) return launch_fused_cfg<DT, 64, 4>(a, grid, s);
+  }
+  return CHUNKKV_ERR_UNSUPPORTED;
 }
 
 }  // namespace ckv

@@ -41,6 +41,7 @@ namespace ckv {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kNegBig = -1.0e30f;
@@ -50,11 +51,17 @@ constexpr int kLoadsPerWave = kTileBytes / 1024 / (kThreads / 64);  // 1 KB load
 constexpr int kScoreMiscBytes = 4 * kSuperKeys * 4 + kSuperKeys * 4 + kMaxRows * 4;
 constexpr int kScoreLdsBytes = kRing * kTileBytes + kScoreMiscBytes;
 
+// 16-bit storage types share every layout (8 elements per 16-byte fragment); only the MFMA differs
+constexpr bool is_16bit(int dt) { return dt == CHUNKKV_BF16 || dt == CHUNKKV_F16; }
+
 template <int DT>
 __device__ __forceinline__ void mma(f32x16 &acc, const u32x4 &a, const u32x4 &b) {
   if constexpr (DT == CHUNKKV_BF16) {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
                                                   acc, 0, 0, 0);
+  } else if constexpr (DT == CHUNKKV_F16) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b),
+                                                 acc, 0, 0, 0);
   } else {
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
@@ -79,7 +86,7 @@ __device__ __forceinline__ void lds_barrier() {
 // (four row blocks per wavefront; fp32 operands at head_dim 128).
 template <int DT, int HD, int NQW, int WQ, int PASS>
 __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD == 128)) ? 1 : 2)) void score_kernel(ScoreArgs a) {
-  constexpr int ESZ = DT == CHUNKKV_BF16 ? 2 : 4;
+  constexpr int ESZ = is_16bit(DT) ? 2 : 4;
   constexpr int ROWB = HD * ESZ;
   constexpr int NSEG = ROWB / 16;
   constexpr int NKS = ROWB / 32;
@@ -272,8 +279,8 @@ __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD ==
   // One pipeline step (see the file header).  HAS_PREV / MASKED are compile-time so that the MFMAs,
   // the fragment reads and the epilogue form one basic block the scheduler can interleave.
   // pass 1: the accumulator start values stay in registers where the register file has room for them
-  // (bf16: every geometry; fp32 operands are twice as large), otherwise they are re-read from LDS per step
-  constexpr bool kStartInRegs = PASS == 1 && DT == CHUNKKV_BF16;
+  // (16-bit types: every geometry; fp32 operands are twice as large), otherwise they are re-read from LDS per step
+  constexpr bool kStartInRegs = PASS == 1 && is_16bit(DT);
   f32x16 start[kStartInRegs ? NQW : 1];
   u32x4 kf[NKS];
   auto step = [&](int b, f32x16 (&cur)[NQW], f32x16 (&prev)[NQW], auto has_prev_c, auto masked_c) {
@@ -314,7 +321,7 @@ __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD ==
         kf[ks] = *frag_at(boff_next, ks);
       }
       if constexpr (HAS_PREV) epilogue(prev, b - 1, masked_c);
-      if constexpr (DT == CHUNKKV_BF16 && HAS_PREV) {
+      if constexpr (is_16bit(DT) && HAS_PREV) {
         // one MFMA, then its share of the epilogue's VALU instructions; a fragment read per MFMA group
         constexpr int kValuPerMfma = (NQW * 16 * 7 / 2) / (NKS * NQW) + 1;
 #pragma unroll

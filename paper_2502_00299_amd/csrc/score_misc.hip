@@ -5,13 +5,16 @@
 namespace ckv {
 
 int launch_score_bf16(int pass, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_score_f16(int pass, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
 int launch_score_f32(int pass, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_score_fused_bf16(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_score_fused_f16(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
 
 bool score_geometry(int dtype, int head_dim, int rows, ScoreGeom *g) {
-  if (dtype != CHUNKKV_F32 && dtype != CHUNKKV_BF16) return false;
+  if (dtype != CHUNKKV_F32 && dtype != CHUNKKV_BF16 && dtype != CHUNKKV_F16) return false;
   if (head_dim != 64 && head_dim != 128) return false;
   if (rows < 1 || rows > kMaxRows) return false;
-  g->row_bytes = head_dim * (dtype == CHUNKKV_BF16 ? 2 : 4);
+  g->row_bytes = head_dim * elem_bytes(dtype);
   g->tile_keys = kTileBytes / g->row_bytes;
   g->nq_blocks = (rows + 31) / 32;
   if (g->nq_blocks == 1) { g->nqw = 1; g->wq = 1; }
@@ -26,8 +29,16 @@ bool score_geometry(int dtype, int head_dim, int rows, ScoreGeom *g) {
 int launch_score_pass(int pass, int dtype, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid,
                       hipStream_t s) {
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return CHUNKKV_OK;
-  return dtype == CHUNKKV_BF16 ? launch_score_bf16(pass, head_dim, g, a, grid, s)
-                               : launch_score_f32(pass, head_dim, g, a, grid, s);
+  if (dtype == CHUNKKV_BF16) return launch_score_bf16(pass, head_dim, g, a, grid, s);
+  if (dtype == CHUNKKV_F16) return launch_score_f16(pass, head_dim, g, a, grid, s);
+  return launch_score_f32(pass, head_dim, g, a, grid, s);
+}
+
+int launch_score_fused(int dtype, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s) {
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return CHUNKKV_OK;
+  if (dtype == CHUNKKV_BF16) return launch_score_fused_bf16(head_dim, g, a, grid, s);
+  if (dtype == CHUNKKV_F16) return launch_score_fused_f16(head_dim, g, a, grid, s);
+  return CHUNKKV_ERR_UNSUPPORTED;
 }
 
 // ref_r = max_r + log2(sum_r) over all key ranges of a problem.  Four lanes share a row: each merges a

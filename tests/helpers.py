@@ -17,12 +17,12 @@ def make_problem(pkg, wl: W.Workload, li: W.LayerInputs, n_keep=None, **kw):
     if n_keep is None:
         n_keep = [W.keep_budget(L, wl.window, wl.keep_pct) for L in li.seqlens]
     return pkg.Problem(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
-                       pkg.F32 if wl.dtype == "f32" else pkg.BF16, list(li.seqlens), list(n_keep),
+                       {"f32": pkg.F32, "bf16": pkg.BF16, "f16": pkg.F16}[wl.dtype], list(li.seqlens), list(n_keep),
                        list(li.kv_base), li.kv_stride_head, li.kv_stride_tok, **kw)
 
 
 def seq_arrays(wl: W.Workload, li: W.LayerInputs, b: int):
-    """Stored bits of sequence b as numpy: q [Hq][w][d], k, v [Hkv][L][d] (uint16 for bf16)."""
+    """Stored bits of sequence b as numpy: q [Hq][w][d], k, v [Hkv][L][d] (uint16 for bf16, float16 for fp16)."""
     q = W.tensor_bits(li.q[b])
     k = W.tensor_bits(li.seq_view(li.k, b, wl.n_kv_heads, wl.head_dim))
     v = W.tensor_bits(li.seq_view(li.v, b, wl.n_kv_heads, wl.head_dim))

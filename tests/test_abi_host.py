@@ -60,6 +60,14 @@ def test_workspace_size_is_positive_and_grows_with_layers(lib):
     assert 0 < a < c < b
 
 
+def test_every_storage_type_is_accepted(lib):
+    """fp32, bf16 and fp16 caches pass validation; the 16-bit types need the same workspace."""
+    sizes = {dt: pkg.chunkkv_workspace_bytes(good(dtype=dt), 4, 2) for dt in (pkg.F32, pkg.BF16, pkg.F16)}
+    assert all(v > 0 for v in sizes.values()) and sizes[pkg.BF16] == sizes[pkg.F16]
+    assert (pkg.F32, pkg.BF16, pkg.F16) == (0, 1, 2)          # the enum of the header
+    assert score_rc(lib, good(dtype=pkg.F16), ws=None) == 4   # argument checks reach the workspace check
+
+
 @pytest.mark.parametrize("kw,status", [
     (dict(n_q_heads=30), 2),                       # Hq % Hkv != 0
     (dict(window=0), 2),

@@ -70,6 +70,15 @@ SCORE_CASES = {
     "bf16_chunk_gt_tile": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(1200,), chunk=300, n_spans=(4,)),
     "bf16_P0": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(32,), n_spans=(0,)),
     "bf16_P_lt_chunk": small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(37,), n_spans=(0,)),
+    # fp16 caches (the paper's storage type, Eq. 1): the 16-bit kernels with the fp16 matrix instruction
+    "f16_8k": small("llama8b_8k", dtype="f16"),
+    "f16_rows32": small("llama8b_8k", dtype="f16", n_q_heads=2, n_kv_heads=2, window=32, seqlens=(1000,), n_spans=(5,)),
+    "f16_rows224_g7": small("ragged_b8", dtype="f16", seqlens=(2049, 517), n_spans=(10, 2), n_layers=1),
+    "f16_rows256_w64": small("llama8b_128k_stack", dtype="f16", seqlens=(4100,), n_spans=(20,), n_layers=1),
+    "f16_d64_rows256_c14": small("llama8b_8k", dtype="f16", n_q_heads=8, n_kv_heads=2, head_dim=64, window=64,
+                                 seqlens=(2100,), chunk=14, n_spans=(8,)),
+    "f16_rows512_c3": small("llama8b_8k", dtype="f16", n_q_heads=16, n_kv_heads=2, window=64, seqlens=(700,), chunk=3,
+                            n_spans=(4,)),
 }
 
 
@@ -232,6 +241,7 @@ STACK_CASES = {
     "bf16_4k_x5": (small("llama8b_32k_stack", seqlens=(4096,), n_spans=(20,), n_layers=5), [1, 2, 4, 7]),
     "ragged_x4": (small("ragged_b8", seqlens=(1500, 640, 2304), n_spans=(7, 3, 11), n_layers=4, chunk=5, keep_pct=30), [1, 3]),
     "w64_20pct_x2": (small("llama8b_128k_stack", seqlens=(3000,), n_spans=(9,), n_layers=2, keep_pct=20), [2]),
+    "f16_4k_x4": (small("llama8b_128k_stack", dtype="f16", seqlens=(4096,), n_spans=(20,), n_layers=4), [1, 2]),
 }
 
 
@@ -301,7 +311,7 @@ def device_lse(wl, li, shift_head=None):
     return out
 
 
-LSE_CASES = ["tiny_f32", "f32_rows160", "bf16_8k", "bf16_rows32", "bf16_rows224_g7", "bf16_rows256_w64",
+LSE_CASES = ["f16_8k", "f16_rows256_w64", "tiny_f32", "f32_rows160", "bf16_8k", "bf16_rows32", "bf16_rows224_g7", "bf16_rows256_w64",
              "bf16_d64_rows256_c14", "bf16_rows512", "bf16_chunk_gt_tile", "bf16_P0", "bf16_P_lt_chunk"]
 
 
@@ -529,7 +539,7 @@ def test_scores_under_extreme_logit_spread(lib, scoring_path, kscale):
 
 
 # ------------------------------------------------------------------ seeded sweep of random shapes
-def _random_cases(n=24, seed=20250299):
+def _random_cases(n=24, seed=20250299, force_dtype=None):
     r = np.random.default_rng(seed)
     cases = []
     while len(cases) < n:
@@ -544,17 +554,19 @@ def _random_cases(n=24, seed=20250299):
         lens = tuple(int(w + 1 + r.integers(0, 4000)) for _ in range(B))
         pct = int(r.choice([5, 10, 20, 35, 100]))
         dtype = "f32" if (r.random() < 0.15 and d == 64) else "bf16"
+        dtype = force_dtype or dtype
         cases.append(dict(n_q_heads=g * hkv, n_kv_heads=hkv, head_dim=d, window=w, chunk=c, seqlens=lens,
                           n_spans=tuple(max(1, L // 300) for L in lens), keep_pct=pct, dtype=dtype, n_layers=2,
                           layout="nhd" if B > 1 else str(r.choice(["hnd", "nhd"]))))
     return cases
 
 
-@pytest.mark.parametrize("idx", range(24))
+@pytest.mark.parametrize("idx", range(24 + 10))
 def test_random_shapes_match_oracle(lib, idx):
     """Scores, selection and gather of 24 seeded random geometries (row counts 8..512, both head dims, chunk
-    sizes with and without a short period, ragged batches, both layouts) against the oracle."""
-    kw = _random_cases()[idx]
+    sizes with and without a short period, ragged batches, both layouts) against the oracle, and of 10 more
+    with fp16 caches."""
+    kw = _random_cases()[idx] if idx < 24 else _random_cases(10, 20250300, "f16")[idx - 24]
     wl = W.get_workload("llama8b_8k").with_(**kw)
     N, R, B, Hk = 2, 2, wl.batch, wl.n_kv_heads
     print(f"case {idx}: {kw}", flush=True)

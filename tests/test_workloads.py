@@ -49,6 +49,17 @@ def test_ragged_layout_views():
     assert np.array_equal(wlmod.bf16_bits_to_f64(bits), li.k.double().numpy())
 
 
+def test_fp16_layers_widen_exactly():
+    wl = wlmod.get_workload("llama8b_8k").with_(dtype="f16", seqlens=(100,), n_spans=(1,), n_layers=1)
+    li = wlmod.make_layer(wl, 0)
+    assert li.k.dtype == torch.float16 and li.q.dtype == torch.float16 and wl.elem_bytes == 2
+    bits = wlmod.tensor_bits(li.k)
+    assert bits.dtype == np.float16 and np.array_equal(bits.astype(np.float64), li.k.double().numpy())
+    # same draw as the bf16 workload before rounding: both round one fp32 tensor
+    lb = wlmod.make_layer(wl.with_(dtype="bf16"), 0)
+    assert float((li.k.float() - lb.k.float()).abs().max()) < 0.05
+
+
 def test_real_ragged_lengths_in_range():
     wl = wlmod.get_workload("ragged_b8")
     assert wl.batch == 8 and all(4096 <= L <= 65536 for L in wl.seqlens)

@@ -41,7 +41,7 @@ class Workload:
     window: int
     chunk: int
     keep_pct: int
-    dtype: str  # "f32" | "bf16"
+    dtype: str  # "f32" | "bf16" | "f16"
     n_layers: int
     n_spans: Tuple[int, ...]  # per sequence
     span_len: Tuple[int, int]
@@ -59,7 +59,7 @@ class Workload:
 
     @property
     def torch_dtype(self):
-        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+        return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.dtype]
 
     @property
     def elem_bytes(self) -> int:
@@ -197,7 +197,7 @@ def make_layer(wl: Workload, layer: int, device="cpu") -> LayerInputs:
 
 
 def tensor_bits(t: torch.Tensor) -> np.ndarray:
-    """Host copy of a tensor's stored bits: float32 array, or uint16 array for bf16."""
+    """Host copy of a tensor's stored bits: float32 or float16 array, or uint16 array for bf16."""
     t = t.detach().to("cpu").contiguous()
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view(np.uint16).copy()
