@@ -31,6 +31,11 @@ Readings taken where the paper is silent or its listings disagree
   R8  Kept tokens keep their original order; the window comes last.
   R15 The whole-chunk variant (Algorithm 3 as printed): k = min(floor(n_keep/c), C)
       chunks, none cut; the kept count then depends on the data (ragged tail).
+  R16 Decoding over the compressed cache (the stage whose cache Eq. 1 sizes and
+      whose latency Section 4.4 tabulates) is ordinary scaled-dot-product
+      attention of ONE new query token per head over every token of K', V':
+      softmax(q K'^T / sqrt(d)) V', query head i reading kv-head i // g; the
+      paper does not restate it.
   R13 Caller-supplied row normalisation (the variant for callers that run behind
       a fused attention kernel): the natural log-sum-exp of the scaled logits
       over the keys the row sees, window keys up to its own position included.
@@ -45,7 +50,10 @@ scores keep tokens [0, n_keep); nesting of kept sets; identity at n_keep = P;
 R = 1 equals per-layer compression; R >= N reuses layer 0 everywhere; the
 log-sum-exp equals a library logsumexp over the visible logits, scores from it
 equal the plain scores, and a shift of the log-sum-exp scales them by exp(-shift);
-the Jaccard similarity is pinned on hand-counted overlaps.
+the Jaccard similarity is pinned on hand-counted overlaps; decode attention
+is pinned on one token (returns its value row), identical keys (mean of the
+value rows), a dominant key, a library scaled-dot-product attention, explicit
+loops, a library logsumexp, and the rule that merges two partial results.
 The paper prints no worked numeric example of this path, so parity on real
 prompts is unpinned; everything above is pinned by mathematics only.
 """
@@ -247,6 +255,31 @@ def compact(k: np.ndarray, v: np.ndarray, sel_chunk: Sequence[np.ndarray], sel_l
         ko.append(k[h][idx])
         vo.append(v[h][idx])
     return np.stack(ko), np.stack(vo)
+
+
+def decode_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[float] = None):
+    """One decoding step over a (compressed) cache, reading R16.
+
+    q: [Hq][d], one new query token per head; k, v: [Hkv][n][d], every token visible.
+    Returns (out [Hq][d], lse [Hq]): out_i = sum_t p_it v_t with p_i = softmax_t(scale * q_i . k_t) over
+    the n tokens of kv-head i // g, and lse_i = ln sum_t exp(scale * q_i . k_t).
+    """
+    q, k, v = widen(q), widen(k), widen(v)
+    Hq, d = q.shape
+    Hkv, n, _ = k.shape
+    g = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros((Hq, d))
+    lse = np.zeros(Hq)
+    for i in range(Hq):
+        h = i // g
+        s = (k[h] @ q[i]) * scale          # [n] logits
+        m = s.max()
+        e = np.exp(s - m)
+        out[i] = (e / e.sum()) @ v[h]
+        lse[i] = m + math.log(e.sum())
+    return out, lse
 
 
 def compress_layer(q_obs, k, v, w: int, c: int, n_keep: int, scale: Optional[float] = None):

@@ -407,3 +407,93 @@ def test_whole_chunk_selection_equals_exact_budget_when_nothing_is_cut():
     assert a[0].tolist() == b[0].tolist() and a[1].tolist() == b[1].tolist()
     # a budget that is no multiple of c: the whole-chunk rule keeps floor(n_keep / c) chunks
     assert len(orc.chunk_topk_whole(scores, P, c, 47)[0]) == 4 and int(orc.chunk_topk(scores, P, c, 47)[1].sum()) == 47
+
+
+# ------------------------------------------------------------------ decode attention over the compressed cache
+def _rand_decode(seed, Hq=6, Hkv=2, n=37, d=8):
+    r = np.random.default_rng(seed)
+    return r.normal(size=(Hq, d)), r.normal(size=(Hkv, n, d)), r.normal(size=(Hkv, n, d))
+
+
+def test_decode_one_token_returns_its_value_row():
+    q, k, v = _rand_decode(0, n=1)
+    out, lse = orc.decode_attention(q, k, v)
+    for i in range(6):
+        assert np.allclose(out[i], v[i // 3, 0], rtol=0, atol=1e-15)
+        assert math.isclose(lse[i], float(q[i] @ k[i // 3, 0]) / math.sqrt(8), rel_tol=1e-13, abs_tol=1e-13)
+
+
+def test_decode_identical_keys_average_the_value_rows():
+    q, k, v = _rand_decode(1)
+    k[:] = k[:, :1]                                   # every token of a head carries the same key
+    out, lse = orc.decode_attention(q, k, v)
+    for i in range(6):
+        assert np.allclose(out[i], v[i // 3].mean(axis=0), rtol=1e-13, atol=1e-13)
+        assert math.isclose(lse[i], float(q[i] @ k[i // 3, 0]) / math.sqrt(8) + math.log(37), rel_tol=1e-12)
+
+
+def test_decode_dominant_key_pins_scale_and_head_map():
+    """Head 4 (kv-head 1 when g = 3) meets one key aligned with it: weight 1/(1 + (n-1) exp(-scale*|q|^2))."""
+    Hq, Hkv, n, d = 6, 2, 9, 16
+    q = np.zeros((Hq, d)); k = np.zeros((Hkv, n, d)); v = np.random.default_rng(2).normal(size=(Hkv, n, d))
+    q[4, 3] = 5.0
+    k[1, 6, 3] = 5.0                                   # only kv-head 1 holds the matching key
+    out, _ = orc.decode_attention(q, k, v)
+    pw = 1.0 / (1.0 + (n - 1) * math.exp(-25.0 / 4.0))  # scale = 1/sqrt(16)
+    rest = (v[1].sum(axis=0) - v[1, 6]) * (1 - pw) / (n - 1)
+    assert np.allclose(out[4], pw * v[1, 6] + rest, rtol=1e-12, atol=1e-12)
+    assert np.allclose(out[1], v[0].mean(axis=0), rtol=1e-12, atol=1e-12)   # a zero query averages kv-head 0
+    out2, _ = orc.decode_attention(q, k, v, scale=1.0)
+    pw2 = 1.0 / (1.0 + (n - 1) * math.exp(-25.0))
+    assert np.allclose(out2[4], pw2 * v[1, 6] + (v[1].sum(axis=0) - v[1, 6]) * (1 - pw2) / (n - 1), rtol=1e-12)
+
+
+def test_decode_equals_library_attention_and_logsumexp():
+    import torch
+    import torch.nn.functional as F
+    q, k, v = _rand_decode(3, Hq=8, Hkv=2, n=53, d=16)
+    out, lse = orc.decode_attention(q, k, v)
+    tq = torch.from_numpy(q)[None, :, None, :]                         # [1][Hq][1][d]
+    tk = torch.from_numpy(k).repeat_interleave(4, dim=0)[None]         # kv-head h serves heads 4h..4h+3
+    tv = torch.from_numpy(v).repeat_interleave(4, dim=0)[None]
+    ref = F.scaled_dot_product_attention(tq, tk, tv)[0, :, 0].numpy()
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
+    for i in range(8):
+        assert math.isclose(lse[i], float(logsumexp(k[i // 4] @ q[i] / 4.0)), rel_tol=1e-13)
+
+
+def test_decode_equals_explicit_loops_on_tiny_input():
+    q, k, v = _rand_decode(4, Hq=4, Hkv=2, n=5, d=3)
+    out, _ = orc.decode_attention(q, k, v, scale=0.7)
+    for i in range(4):
+        h = i // 2
+        wts = [math.exp(0.7 * sum(q[i, e] * k[h, t, e] for e in range(3))) for t in range(5)]
+        for e in range(3):
+            assert math.isclose(out[i, e], sum(wts[t] * v[h, t, e] for t in range(5)) / sum(wts), rel_tol=1e-12, abs_tol=1e-14)
+
+
+def test_decode_partial_results_merge_by_their_log_sum_exps():
+    """Attention over a cache split in two equals the lse-weighted mean of the parts (what lets key ranges be
+    processed independently); a wrong lse or a transposed operand breaks it."""
+    q, k, v = _rand_decode(5, n=41)
+    out, lse = orc.decode_attention(q, k, v)
+    oa, la = orc.decode_attention(q, k[:, :17], v[:, :17])
+    ob, lb = orc.decode_attention(q, k[:, 17:], v[:, 17:])
+    wa = 1.0 / (1.0 + np.exp(lb - la))
+    assert np.allclose(out, wa[:, None] * oa + (1 - wa)[:, None] * ob, rtol=1e-12, atol=1e-13)
+    assert np.allclose(lse, np.logaddexp(la, lb), rtol=1e-13)
+
+
+def test_decode_widens_stored_16_bit_values_exactly():
+    import torch
+    r = np.random.default_rng(6)
+    qf, kf, vf = r.normal(size=(2, 8)), r.normal(size=(1, 11, 8)), r.normal(size=(1, 11, 8))
+    want, _ = orc.decode_attention(torch.tensor(qf).bfloat16().double().numpy(), torch.tensor(kf).bfloat16().double().numpy(),
+                                   torch.tensor(vf).bfloat16().double().numpy())
+    bits = lambda x: torch.tensor(x).bfloat16().view(torch.int16).numpy().view(np.uint16)
+    got, _ = orc.decode_attention(bits(qf), bits(kf), bits(vf))
+    assert np.array_equal(got, want)
+    got16, _ = orc.decode_attention(qf.astype(np.float16), kf.astype(np.float16), vf.astype(np.float16))
+    want16, _ = orc.decode_attention(qf.astype(np.float16).astype(np.float64), kf.astype(np.float16).astype(np.float64),
+                                     vf.astype(np.float16).astype(np.float64))
+    assert np.array_equal(got16, want16)
