@@ -171,6 +171,26 @@ int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t
  * reads the kept count of a head as the sum of its sel_len entries.                                        */
 int chunkkv_set_whole_chunks(int32_t enable);
 
+/* Decoding over the (compressed) cache: the stage whose cache Eq. 1 sizes and whose latency Section 4.4
+ * tabulates; Algorithm 1's output K', V' is its input.  One new query token per head attends to every
+ * token of the cache of its kv-head (query head i reads kv-head i / g):
+ *     out[b][i][:] = sum_t softmax_t(scale * q[b][i] . K[b][i/g][t]) * V[b][i/g][t][:]
+ *   compacted   1: k, v are K', V' as written by chunkkv_compact / chunkkv_compress_* (prob->out_base,
+ *               out_stride_*), n_keep_b + w tokens per head; 0: the uncompressed caches (prob->kv_base,
+ *               kv_stride_*), seqlen_b tokens per head
+ *   kv_len      device int32 [B][Hkv] or NULL: tokens to attend to per (sequence, kv-head), clamped to the
+ *               count above (whole-chunk selection keeps a data-dependent count); 0 tokens give out = 0
+ *   q           device [B][Hq][d] in prob->dtype, 16-byte aligned
+ *   out         device float [B][Hq][d]
+ *   lse         device float [B][Hq] or NULL: natural log of the softmax denominator (-inf for 0 tokens)
+ *   workspace   device, chunkkv_decode_workspace_bytes(prob, compacted) bytes, contents scratch
+ * Products and sums are fp32 (16-bit inputs are exact in fp32).  Asynchronous on `stream`; two launches;
+ * no allocation.  Errors as for chunkkv_score.                                                          */
+size_t chunkkv_decode_workspace_bytes(const chunkkv_problem *prob, int32_t compacted);
+int chunkkv_decode_attention(const chunkkv_problem *prob, int32_t compacted, const int32_t *kv_len, const void *q,
+                             const void *k, const void *v, float *out, float *lse, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
 /* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 and fp16 caches,
  * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
  * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a
@@ -196,9 +216,9 @@ int chunkkv_set_overlap(int32_t sets);
  * milliseconds and the number of launches:
  *   0 score pass 0 (softmax statistics) or the single-pass kernel   1 statistics merge
  *   2 score pass 1 (importance, chunk sums) or the single-pass row reduction
- *   3 chunk sums for c larger than a key tile   4 chunk selection   5 compaction
+ *   3 chunk sums for c larger than a key tile   4 chunk selection   5 compaction   6 decode attention
  * total_ms and launches are host arrays of CHUNKKV_TIMING_KINDS entries.  Not thread-safe.          */
-#define CHUNKKV_TIMING_KINDS 6
+#define CHUNKKV_TIMING_KINDS 7
 int chunkkv_timing_begin(int32_t max_records);
 int chunkkv_timing_end(double *total_ms, int64_t *launches);
 

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     chunkkv_compress_layer,
     chunkkv_compress_stack,
     chunkkv_compress_stack_lse,
+    chunkkv_decode_attention,
+    chunkkv_decode_workspace_bytes,
     chunkkv_jaccard,
     chunkkv_score,
     chunkkv_score_lse,

@@ -20,11 +20,12 @@ LIB_PATH = os.path.join(_PKG, "libchunkkv.so")
 F32, BF16, F16 = 0, 1, 2
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
-           "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_set_overlap", "chunkkv_set_single_pass",
+           "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_decode_workspace_bytes", "chunkkv_decode_attention",
+           "chunkkv_set_overlap", "chunkkv_set_single_pass",
            "chunkkv_set_whole_chunks",
            "chunkkv_timing_begin",
            "chunkkv_timing_end")
-TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact")
+TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact", "decode")
 
 
 class ChunkKVError(RuntimeError):
@@ -152,6 +153,11 @@ def load_library(path: Optional[str] = None):
                                            i32p, i32p, i32p, vp, C.c_size_t, vp]
     lib.chunkkv_jaccard.restype = C.c_int
     lib.chunkkv_jaccard.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, i32p, i32p, f32p, vp]
+    lib.chunkkv_decode_workspace_bytes.restype = C.c_size_t
+    lib.chunkkv_decode_workspace_bytes.argtypes = [C.POINTER(_CProblem), C.c_int32]
+    lib.chunkkv_decode_attention.restype = C.c_int
+    lib.chunkkv_decode_attention.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, vp, vp, vp, f32p, f32p, vp,
+                                             C.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -255,6 +261,18 @@ def chunkkv_jaccard(prob: Problem, n_groups: int, sel_chunk, sel_len, sel_count,
     cp = prob.as_c()
     _check(load_library().chunkkv_jaccard(C.byref(cp), n_groups, _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count),
                                           _ptr(jaccard), _stream(stream)), "chunkkv_jaccard")
+
+
+def chunkkv_decode_workspace_bytes(prob: Problem, compacted: bool = True) -> int:
+    return int(load_library().chunkkv_decode_workspace_bytes(C.byref(prob.as_c()), 1 if compacted else 0))
+
+
+def chunkkv_decode_attention(prob: Problem, compacted: bool, kv_len, q, k, v, out, lse, workspace, stream=None) -> None:
+    cp = prob.as_c()
+    _check(load_library().chunkkv_decode_attention(
+        C.byref(cp), 1 if compacted else 0, _ptr(kv_len), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
+        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
+        "chunkkv_decode_attention")
 
 
 def chunkkv_set_single_pass(enable: bool) -> None:

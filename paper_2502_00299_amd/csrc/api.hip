@@ -26,7 +26,8 @@ struct Plan {
 };
 
 // ---- optional per-kernel timing (chunkkv_timing_begin / chunkkv_timing_end) -----------------------
-enum Kind { kStats = 0, kCombine, kColsum, kChunkSums, kTopk, kCompact, kKinds };
+enum Kind { kStats = 0, kCombine, kColsum, kChunkSums, kTopk, kCompact, kDecode, kKinds };
+static_assert(kKinds == CHUNKKV_TIMING_KINDS, "timing kinds of the header");
 struct Timing {
   bool on = false;
   int cap = 0, used = 0;
@@ -112,6 +113,39 @@ int check_problem(const chunkkv_problem *p, bool need_out) {
 }
 
 bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }
+
+// Key-range split and workspace of the decode-attention call: a pure function of the problem.  About
+// kDecodeTargetWorkgroups workgroups per launch, never fewer than kDecodeMinRows rows per range.
+constexpr int kDecodeTargetWorkgroups = 1024;
+constexpr int kDecodeMinRows = 256;
+struct DecodePlan {
+  int n_split, rows_per_split;
+  size_t off_ml, off_o, total;
+};
+int decode_plan(const chunkkv_problem *p, bool compacted, DecodePlan *pl) {
+  int64_t n_max = 1;
+  for (int b = 0; b < p->batch; ++b) {
+    const int64_t n = compacted ? (int64_t)p->n_keep[b] + p->window : p->seqlen[b];
+    n_max = n > n_max ? n : n_max;
+  }
+  const int g = p->n_q_heads / p->n_kv_heads;
+  const int G = decode_heads_per_wg(p->dtype, g), nz = (g + G - 1) / G;
+  const int nb = p->batch < kMaxBatchPerLaunch ? p->batch : kMaxBatchPerLaunch;
+  int64_t per_head = kDecodeTargetWorkgroups / ((int64_t)nb * p->n_kv_heads * nz);
+  per_head = per_head < 1 ? 1 : per_head;
+  const int64_t by_rows = (n_max + kDecodeMinRows - 1) / kDecodeMinRows;
+  int64_t n_split = per_head < by_rows ? per_head : by_rows;
+  int64_t rows = (n_max + n_split - 1) / n_split;
+  rows = (rows + 127) / 128 * 128;
+  n_split = (n_max + rows - 1) / rows;
+  pl->n_split = (int)n_split;
+  pl->rows_per_split = (int)rows;
+  const size_t heads = (size_t)p->batch * p->n_q_heads;
+  pl->off_ml = 0;
+  pl->off_o = align256(heads * n_split * sizeof(float2));
+  pl->total = pl->off_o + align256(heads * n_split * p->head_dim * sizeof(float));
+  return CHUNKKV_OK;
+}
 
 // Workspace layout and key-range split; a pure function of (problem, n_layers, reuse).
 int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
@@ -539,6 +573,45 @@ int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t
   if (!sel_chunk || !sel_len || !sel_count || !jaccard) return CHUNKKV_ERR_NULL;
   return launch_jaccard(sel_chunk, sel_len, sel_count, prob->sel_cap, prob->chunk, prob->batch * prob->n_kv_heads,
                         n_groups - 1, jaccard, (hipStream_t)stream);
+}
+
+size_t chunkkv_decode_workspace_bytes(const chunkkv_problem *prob, int32_t compacted) {
+  DecodePlan pl;
+  if (check_problem(prob, compacted != 0) || decode_plan(prob, compacted != 0, &pl)) return 0;
+  return pl.total;
+}
+
+int chunkkv_decode_attention(const chunkkv_problem *prob, int32_t compacted, const int32_t *kv_len, const void *q,
+                             const void *k, const void *v, float *out, float *lse, void *workspace,
+                             size_t workspace_bytes, void *stream) {
+  int rc = check_problem(prob, compacted != 0);
+  if (rc) return rc;
+  if (!q || !k || !v || !out) return CHUNKKV_ERR_NULL;
+  if (misaligned(q) || misaligned(k) || misaligned(v)) return CHUNKKV_ERR_SHAPE;
+  DecodePlan pl;
+  if ((rc = decode_plan(prob, compacted != 0, &pl))) return rc;
+  if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const float scale = prob->softmax_scale > 0.f ? prob->softmax_scale : 1.0f / sqrtf((float)prob->head_dim);
+  for (int b0 = 0; b0 < prob->batch; b0 += kMaxBatchPerLaunch) {
+    const int nb = prob->batch - b0 < kMaxBatchPerLaunch ? prob->batch - b0 : kMaxBatchPerLaunch;
+    DecodeArgs a{};
+    a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.kv_len = kv_len;
+    a.part_ml = (float2 *)((char *)workspace + pl.off_ml);
+    a.part_o = (float *)((char *)workspace + pl.off_o);
+    for (int i = 0; i < nb; ++i) {
+      a.n_tok[i] = compacted ? prob->n_keep[b0 + i] + prob->window : prob->seqlen[b0 + i];
+      a.base[i] = compacted ? prob->out_base[b0 + i] : prob->kv_base[b0 + i];
+    }
+    a.stride_head = compacted ? prob->out_stride_head : prob->kv_stride_head;
+    a.stride_tok = compacted ? prob->out_stride_tok : prob->kv_stride_tok;
+    a.batch0 = b0; a.n_q_heads = prob->n_q_heads; a.n_kv_heads = prob->n_kv_heads;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.n_split = pl.n_split; a.rows_per_split = pl.rows_per_split;
+    { Timed t(kDecode, s); rc = launch_decode(prob->dtype, prob->head_dim, a, nb, s); }
+    if (rc) return rc;
+  }
+  return CHUNKKV_OK;
 }
 
 int chunkkv_set_whole_chunks(int32_t enable) {

@@ -1,0 +1,286 @@
+// Decoding over the (compressed) cache: one new query token per head attends to every token of K', V'
+// (the stage whose cache Eq. 1 sizes and whose latency Section 4.4 tabulates; Algorithm 1's output is its
+// input).  out_i = sum_t softmax_t(scale * q_i . k_t) v_t, query head i reading kv-head i / g.
+//
+// Bound by HBM bandwidth: every K and V row is read once, g dot products and g axpys per row are far below
+// the vector ALU's rate, so this is a streaming kernel on the vector ALU, not a matrix-core kernel.  A row
+// (d elements) is spread over LPR = d * element size / 16 lanes, 16 bytes each, so one load instruction of
+// a wavefront reads 64 / LPR consecutive rows as one contiguous piece.  The lanes of a row reduce their
+// partial dot products with DPP adds (no LDS).  Each group of LPR lanes runs its own online softmax over the
+// rows it meets; the groups of a wavefront, the wavefronts of a workgroup and the key ranges of a head are
+// merged afterwards by the usual (max, sum, weighted output) rule, always in the same order.
+// Grid: x = key range, y = (sequence, kv-head), z = batch of G query heads of the kv-head.
+#include "internal.h"
+
+namespace ckv {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kDecodeUnroll = 4;        // row loads of K (and of V) in flight per lane
+constexpr float kDecodeNegBig = -1.0e30f;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __builtin_amdgcn_update_dpp(0.f, x, CTRL, 0xf, 0xf, false);
+}
+// Sum over the LPR lanes that share a row; every lane of the group ends with the same bits.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+  x = dpp_add<0xB1>(x);                          // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                          // quad_perm [2,3,0,1]
+  if constexpr (LPR >= 8) x = dpp_add<0x141>(x);   // row_half_mirror: the other quad of 8 lanes
+  if constexpr (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror: the other half of 16 lanes
+  if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
+// 16 bytes of a row as fp32 values (8 for the 16-bit types, 4 for fp32)
+template <int DT>
+__device__ __forceinline__ void widen16(const u32x4 &r, float (&f)[16 / (DT == CHUNKKV_F32 ? 4 : 2)]) {
+  if constexpr (DT == CHUNKKV_F32) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  } else if constexpr (DT == CHUNKKV_BF16) {
+    const uint32_t d[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[2 * i] = __uint_as_float(d[i] << 16); f[2 * i + 1] = __uint_as_float(d[i] & 0xFFFF0000u); }
+  } else {
+    const uint32_t d[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f16x2 h = __builtin_bit_cast(f16x2, d[i]);
+      f[2 * i] = (float)h[0]; f[2 * i + 1] = (float)h[1];
+    }
+  }
+}
+
+// partial dot product of a lane's 16 bytes of a K row with its 16 bytes of a query row
+template <int DT>
+__device__ __forceinline__ float dot16(const u32x4 &k, const u32x4 &q) {
+  if constexpr (DT == CHUNKKV_F32) {
+    float s = __uint_as_float(k.x) * __uint_as_float(q.x);
+    s = __builtin_fmaf(__uint_as_float(k.y), __uint_as_float(q.y), s);
+    s = __builtin_fmaf(__uint_as_float(k.z), __uint_as_float(q.z), s);
+    return __builtin_fmaf(__uint_as_float(k.w), __uint_as_float(q.w), s);
+  } else if constexpr (DT == CHUNKKV_BF16) {
+    // the pairs are taken from whole-vector casts: a bit cast of a single vector element reads element 0
+    const bf16x8 kk = __builtin_bit_cast(bf16x8, k), qq = __builtin_bit_cast(bf16x8, q);
+    float s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(kk, kk, 0, 1), __builtin_shufflevector(qq, qq, 0, 1), 0.f, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(kk, kk, 2, 3), __builtin_shufflevector(qq, qq, 2, 3), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(kk, kk, 4, 5), __builtin_shufflevector(qq, qq, 4, 5), s, false);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(kk, kk, 6, 7), __builtin_shufflevector(qq, qq, 6, 7), s, false);
+  } else {
+    const f16x8 kk = __builtin_bit_cast(f16x8, k), qq = __builtin_bit_cast(f16x8, q);
+    float s = __builtin_amdgcn_fdot2(__builtin_shufflevector(kk, kk, 0, 1), __builtin_shufflevector(qq, qq, 0, 1), 0.f, false);
+    s = __builtin_amdgcn_fdot2(__builtin_shufflevector(kk, kk, 2, 3), __builtin_shufflevector(qq, qq, 2, 3), s, false);
+    s = __builtin_amdgcn_fdot2(__builtin_shufflevector(kk, kk, 4, 5), __builtin_shufflevector(qq, qq, 4, 5), s, false);
+    return __builtin_amdgcn_fdot2(__builtin_shufflevector(kk, kk, 6, 7), __builtin_shufflevector(qq, qq, 6, 7), s, false);
+  }
+}
+
+// DT: chunkkv_dtype, HD: head dim, G: query heads of the kv-head handled by one workgroup
+template <int DT, int HD, int G>
+__global__ __launch_bounds__(kThreads) void decode_kernel(DecodeArgs a) {
+  constexpr int ESZ = DT == CHUNKKV_F32 ? 4 : 2;
+  constexpr int ROWB = HD * ESZ;
+  constexpr int LPR = ROWB / 16;   // lanes per row
+  constexpr int RPW = 64 / LPR;    // rows per wavefront load
+  constexpr int EPL = 16 / ESZ;    // elements per lane
+  constexpr int U = kDecodeUnroll;
+  constexpr int NW = kThreads / 64;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int grp = lane / LPR, seg = lane % LPR;
+  const int bl = blockIdx.y / a.n_kv_heads, h = blockIdx.y % a.n_kv_heads;
+  const int split = blockIdx.x;
+  const int g = a.n_q_heads / a.n_kv_heads;
+  const int j0 = blockIdx.z * G;  // first query head (within the kv-head's group) of this workgroup
+  const int b = a.batch0 + bl;
+
+  // tokens of this (sequence, kv-head): the capacity of the cache, or the caller's count clamped to it
+  const int cap = pick(a.n_tok, bl);
+  int n = cap;
+  if (a.kv_len != nullptr) {
+    n = a.kv_len[(int64_t)b * a.n_kv_heads + h];
+    n = n < 0 ? 0 : (n > cap ? cap : n);
+  }
+  const int r0 = split * a.rows_per_split;
+  const int r1 = r0 + a.rows_per_split < n ? r0 + a.rows_per_split : n;
+
+  const int64_t head_off = (pick(a.base, bl) + (int64_t)h * a.stride_head) * ESZ;
+  const char *kbase = (const char *)a.k + head_off + seg * 16;
+  const char *vbase = (const char *)a.v + head_off + seg * 16;
+  const int64_t tok = a.stride_tok * ESZ;
+
+  u32x4 qreg[G];
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    qreg[j] = u32x4{0, 0, 0, 0};
+    if (j0 + j < g)
+      qreg[j] = *(const u32x4 *)((const char *)a.q + ((int64_t)b * a.n_q_heads + (int64_t)h * g + j0 + j) * ROWB + seg * 16);
+  }
+  float m[G], l[G], o[G][EPL];
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    m[j] = kDecodeNegBig;
+    l[j] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[j][e] = 0.f;
+  }
+  const float c1 = a.scale_log2e;
+
+  // rows r0 .. r1-1; a step of the workgroup covers NW * U * RPW consecutive rows
+  for (int base = r0 + wave * (U * RPW); base < r1; base += NW * U * RPW) {
+    u32x4 kr[U], vr[U];
+    bool valid[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + u * RPW + grp;
+      valid[u] = row < r1;
+      const int64_t off = (int64_t)(valid[u] ? row : r1 - 1) * tok;  // r1 >= 1 inside the loop
+      kr[u] = *(const u32x4 *)(kbase + off);
+      vr[u] = *(const u32x4 *)(vbase + off);
+    }
+    float s[U][G];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        const float d = row_sum<LPR>(dot16<DT>(kr[u], qreg[j]));
+        s[u][j] = valid[u] ? d * c1 : -3.0e38f;
+      }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      float smax = s[0][j];
+#pragma unroll
+      for (int u = 1; u < U; ++u) smax = fmaxf(smax, s[u][j]);
+      if (__builtin_amdgcn_ballot_w64(smax > m[j]) != 0) {
+        const float m_new = fmaxf(m[j], smax);
+        const float f = __builtin_amdgcn_exp2f(m[j] - m_new);
+        l[j] *= f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[j][e] *= f;
+        m[j] = m_new;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) s[u][j] = __builtin_amdgcn_exp2f(s[u][j] - m[j]);  // now the weight p
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float vf[EPL];
+      widen16<DT>(vr[u], vf);
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        l[j] += s[u][j];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[j][e] = __builtin_fmaf(s[u][j], vf[e], o[j][e]);
+      }
+    }
+  }
+
+  // merge the row groups of the wavefront (lanes that hold the same 16 bytes of the row)
+#pragma unroll
+  for (int x = LPR; x < 64; x *= 2) {
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const float m_o = __shfl_xor(m[j], x), l_o = __shfl_xor(l[j], x);
+      const float M = fmaxf(m[j], m_o);
+      const float fa = __builtin_amdgcn_exp2f(m[j] - M), fb = __builtin_amdgcn_exp2f(m_o - M);
+      l[j] = l[j] * fa + l_o * fb;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[j][e] = o[j][e] * fa + __shfl_xor(o[j][e], x) * fb;
+      m[j] = M;
+    }
+  }
+  // merge the wavefronts through LDS: thread (j, seg) folds the four states in wavefront order
+  __shared__ float s_m[NW][G][LPR], s_l[NW][G][LPR], s_o[NW][G][LPR][EPL];
+  if (grp == 0) {
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      s_m[wave][j][seg] = m[j];
+      s_l[wave][j][seg] = l[j];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s_o[wave][j][seg][e] = o[j][e];
+    }
+  }
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < G * LPR) {
+    const int j = t / LPR, sg = t % LPR;
+    if (j0 + j < g) {
+      float M = s_m[0][j][sg];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][j][sg]);
+      float Lsum = 0.f, acc[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const float f = __builtin_amdgcn_exp2f(s_m[w][j][sg] - M);
+        Lsum += s_l[w][j][sg] * f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += s_o[w][j][sg][e] * f;
+      }
+      const int64_t head = (int64_t)b * a.n_q_heads + (int64_t)h * g + j0 + j;
+      const int64_t slot = head * a.n_split + split;
+      if (sg == 0) a.part_ml[slot] = make_float2(M, Lsum);
+      float *po = a.part_o + slot * HD + sg * EPL;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) po[e] = acc[e];
+    }
+  }
+}
+
+// out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) over the key ranges of one query head, in range order.
+// grid: x = query head of the batch slice; HD threads.
+template <int HD>
+__global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeArgs a) {
+  const int64_t head = (int64_t)a.batch0 * a.n_q_heads + blockIdx.x;
+  const float2 *ml = a.part_ml + head * a.n_split;
+  const float *po = a.part_o + head * a.n_split * HD + threadIdx.x;
+  float M = kDecodeNegBig;
+  for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, ml[s].x);
+  float Lsum = 0.f, acc = 0.f;
+  for (int s = 0; s < a.n_split; ++s) {
+    const float f = __builtin_amdgcn_exp2f(ml[s].x - M);
+    Lsum += ml[s].y * f;
+    acc += po[(int64_t)s * HD] * f;
+  }
+  a.out[head * HD + threadIdx.x] = Lsum > 0.f ? acc / Lsum : 0.f;
+  if (a.lse != nullptr && threadIdx.x == 0)
+    a.lse[head] = Lsum > 0.f ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+}
+
+template <int DT, int HD>
+int launch_decode_hd(const DecodeArgs &a, int batch_slice, int g, hipStream_t s) {
+  const int G = decode_heads_per_wg(DT, g);
+  const dim3 grid(a.n_split, batch_slice * a.n_kv_heads, (g + G - 1) / G);
+  if (grid.x == 0 || grid.y == 0) return CHUNKKV_OK;
+  if (G == 1) hipLaunchKernelGGL((decode_kernel<DT, HD, 1>), grid, dim3(kThreads), 0, s, a);
+  else if (G == 2) hipLaunchKernelGGL((decode_kernel<DT, HD, 2>), grid, dim3(kThreads), 0, s, a);
+  else if (G == 4) hipLaunchKernelGGL((decode_kernel<DT, HD, 4>), grid, dim3(kThreads), 0, s, a);
+  else if constexpr (DT != CHUNKKV_F32) hipLaunchKernelGGL((decode_kernel<DT, HD, 8>), grid, dim3(kThreads), 0, s, a);
+  else return CHUNKKV_ERR_UNSUPPORTED;
+  if (hipGetLastError() != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+  hipLaunchKernelGGL((decode_combine_kernel<HD>), dim3(batch_slice * a.n_q_heads), dim3(HD), 0, s, a);
+  return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
+}
+
+int launch_decode(int dtype, int head_dim, const DecodeArgs &a, int batch_slice, hipStream_t s) {
+  const int g = a.n_q_heads / a.n_kv_heads;
+  if (head_dim == 128) {
+    if (dtype == CHUNKKV_BF16) return launch_decode_hd<CHUNKKV_BF16, 128>(a, batch_slice, g, s);
+    if (dtype == CHUNKKV_F16) return launch_decode_hd<CHUNKKV_F16, 128>(a, batch_slice, g, s);
+    if (dtype == CHUNKKV_F32) return launch_decode_hd<CHUNKKV_F32, 128>(a, batch_slice, g, s);
+  } else if (head_dim == 64) {
+    if (dtype == CHUNKKV_BF16) return launch_decode_hd<CHUNKKV_BF16, 64>(a, batch_slice, g, s);
+    if (dtype == CHUNKKV_F16) return launch_decode_hd<CHUNKKV_F16, 64>(a, batch_slice, g, s);
+    if (dtype == CHUNKKV_F32) return launch_decode_hd<CHUNKKV_F32, 64>(a, batch_slice, g, s);
+  }
+  return CHUNKKV_ERR_UNSUPPORTED;
+}
+
+}  // namespace ckv

@@ -87,6 +87,27 @@ struct CompactArgs {
   int32_t whole_chunks;       // 1: the window follows the kept tokens directly (their count varies per head)
 };
 
+// Decode attention over one layer's cache (decode.hip).  Per-head partial results use the FULL batch index.
+struct DecodeArgs {
+  const void *q, *k, *v;
+  float *out, *lse;           // [batch_total][Hq][d], [batch_total][Hq] or null
+  float2 *part_ml;            // [batch_total * Hq][n_split]  (max in log2 units, sum)
+  float *part_o;              // [batch_total * Hq][n_split][d]
+  const int32_t *kv_len;      // [batch_total][Hkv] tokens to attend to, or null (= n_tok)
+  int32_t n_tok[kMaxBatchPerLaunch];  // tokens the cache of a sequence holds per head
+  int64_t base[kMaxBatchPerLaunch];   // element offset of the sequence in k / v
+  int64_t stride_head, stride_tok;
+  int32_t batch0, n_q_heads, n_kv_heads;
+  float scale_log2e;
+  int32_t n_split, rows_per_split;
+};
+
+// query heads of one kv-head that a decode workgroup serves: 1, 2, 4 or 8 (fp32 caches: at most 4, registers)
+inline int decode_heads_per_wg(int dtype, int g) {
+  const int G = g >= 8 ? 8 : (g > 2 ? 4 : g);
+  return dtype == CHUNKKV_F32 && G > 4 ? 4 : G;
+}
+
 // Reads element i of a small table that travels as a kernel argument.  A chain of selects on the
 // (wavefront-uniform) index keeps the table in scalar registers; a dynamic subscript would make the
 // compiler copy the whole argument struct to scratch memory first.
@@ -121,6 +142,7 @@ int launch_jaccard(const int32_t *sel_chunk, const int32_t *sel_len, const int32
 int launch_lse_refs(const LseArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
 int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s);
+int launch_decode(int dtype, int head_dim, const DecodeArgs &a, int batch_slice, hipStream_t s);
 int launch_compact(int row_bytes, const CompactArgs &a, int n_layers_slice, int batch_slice,
                    int max_entries, hipStream_t s);
 

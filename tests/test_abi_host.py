@@ -168,3 +168,26 @@ def test_layer_and_jaccard_argument_checks(lib):
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         pkg.load_library(str(tmp_path / "nope.so"))
+
+
+def test_decode_argument_checks(lib):
+    p = good(out_base=[0], out_stride_head=848 * 128, out_stride_tok=128)
+    cp = p.as_c()
+    full, comp = pkg.chunkkv_decode_workspace_bytes(p, False), pkg.chunkkv_decode_workspace_bytes(p, True)
+    assert 0 < comp < full                       # fewer key ranges over the 10 % cache
+    f = lib.chunkkv_decode_attention
+    assert f(None, 0, None, FAKE, FAKE, FAKE, FAKE, None, FAKE, full, None) == 1
+    assert f(C.byref(cp), 0, None, None, FAKE, FAKE, FAKE, None, FAKE, full, None) == 1
+    assert f(C.byref(cp), 0, None, FAKE, None, FAKE, FAKE, None, FAKE, full, None) == 1
+    assert f(C.byref(cp), 0, None, FAKE, FAKE, None, FAKE, None, FAKE, full, None) == 1
+    assert f(C.byref(cp), 0, None, FAKE, FAKE, FAKE, None, None, FAKE, full, None) == 1
+    assert f(C.byref(cp), 0, None, C.c_void_p(0x1008), FAKE, FAKE, FAKE, None, FAKE, full, None) == 2
+    assert f(C.byref(cp), 0, None, FAKE, FAKE, FAKE, FAKE, None, None, full, None) == 4
+    assert f(C.byref(cp), 0, None, FAKE, FAKE, FAKE, FAKE, None, FAKE, full - 1, None) == 4
+    assert f(C.byref(cp), 1, None, FAKE, FAKE, FAKE, FAKE, None, FAKE, comp - 1, None) == 4
+    # the compressed layout needs the output geometry of the problem
+    bad_out = good(out_base=[0], out_stride_head=848 * 128, out_stride_tok=100)
+    assert pkg.chunkkv_decode_workspace_bytes(bad_out, True) == 0
+    assert pkg.chunkkv_decode_workspace_bytes(bad_out, False) == full
+    assert f(C.byref(bad_out.as_c()), 1, None, FAKE, FAKE, FAKE, FAKE, None, FAKE, full, None) == 2
+    assert pkg.chunkkv_decode_workspace_bytes(good(head_dim=96), False) == 0
