@@ -139,6 +139,7 @@ def main():
     ap.add_argument("--no-lse", action="store_true", help="skip the caller-supplied log-sum-exp leg")
     ap.add_argument("--no-streaming", action="store_true", help="skip the per-layer streaming-call leg")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
     ap.add_argument("--overlap", type=int, default=0,
                     help="k > 0: score the leader layers in k sets and gather each set on a helper stream")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -329,6 +330,36 @@ def main():
         except Exception as e:
             log(f"streaming leg failed: {e!r}")
 
+    # what the compression buys afterwards: one decoding step's attention (one query token per head, every
+    # layer) over the compressed caches this run produced, and over the uncompressed caches for comparison
+    decode_leg = None
+    if not args.no_decode:
+        try:
+            run_main()
+            qd = [x.q[:, :, -1, :].contiguous() for x in layers]
+            o_d = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+            legs = {}
+            for name, compacted, kk, vv, toks in (("compressed", True, k_out, v_out, [nk + wl.window for nk in n_keep]),
+                                                 ("full", False, ks, vs, list(wl.seqlens))):
+                ws_d = torch.empty(ckv.chunkkv_decode_workspace_bytes(prob, compacted), dtype=torch.uint8, device=dev)
+
+                def run_decode():
+                    for l in range(N):
+                        ckv.chunkkv_decode_attention(prob, compacted, None, qd[l], kk[l], vv[l], o_d, None, ws_d)
+                ms_d, _ = timed(run_decode, args.steps, args.warmup)
+                _, kt_d = timed(run_decode, args.steps, 1, with_kernel_timing=True)
+                nbytes = N * sum(2 * wl.n_kv_heads * t * wl.head_dim * wl.elem_bytes for t in toks)
+                t_k, n_k = kt_d["decode"]
+                legs[name] = {"ms_per_token_all_layers": ms_d, "kernel_ms_per_layer": t_k / max(n_k, 1),
+                              "algorithmic_bytes": nbytes, "achieved_GBps": nbytes / (ms_d * 1e-3) / 1e9,
+                              "kernel_GBps": nbytes / N / (t_k / max(n_k, 1) * 1e-3) / 1e9,
+                              "hbm_frac": nbytes / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+                del ws_d
+            decode_leg = {**legs, "speedup_compressed_vs_full": legs["full"]["ms_per_token_all_layers"] /
+                          legs["compressed"]["ms_per_token_all_layers"]}
+        except Exception as e:
+            log(f"decode leg failed: {e!r}")
+
     out = {
         "metric": "prefix tokens compressed/sec (32-layer stack) + achieved HBM GB/s vs peak",
         "value": value, "unit": "prefix tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -343,6 +374,7 @@ def main():
                       "unit": "GB/s", "frac": stack_gbps / HBM_PEAK_GBPS},
         "roofline_mfma": mfma,
         "kernels_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in kern.items()},
+        "decode_attention": decode_leg,
         "with_caller_lse": lse_leg,
         "streaming_per_layer": stream_leg,
         "hip_graph_replay": graph_leg,

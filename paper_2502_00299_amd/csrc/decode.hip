@@ -234,24 +234,50 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeArgs a) {
   }
 }
 
-// out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) over the key ranges of one query head, in range order.
-// grid: x = query head of the batch slice; HD threads.
+// out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) over the key ranges of one query head.
+// grid: x = query head of the batch slice; 256 threads: a thread owns four consecutive output elements
+// and every kCombineGroups-th key range; the groups are folded through LDS in group order, so the
+// summation order is fixed.
+constexpr int kCombineThreads = 256;
 template <int HD>
-__global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(DecodeArgs a) {
+  constexpr int TPR = HD / 4;                     // threads per partial row
+  constexpr int NG = kCombineThreads / TPR;       // key-range groups
   const int64_t head = (int64_t)a.batch0 * a.n_q_heads + blockIdx.x;
   const float2 *ml = a.part_ml + head * a.n_split;
-  const float *po = a.part_o + head * a.n_split * HD + threadIdx.x;
+  const int t = threadIdx.x, col = t % TPR, grp = t / TPR;
+  __shared__ float s_red[kCombineThreads / 64];
+  __shared__ float s_acc[NG][HD + 1];
+  // maximum over the key ranges
   float M = kDecodeNegBig;
-  for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, ml[s].x);
-  float Lsum = 0.f, acc = 0.f;
-  for (int s = 0; s < a.n_split; ++s) {
-    const float f = __builtin_amdgcn_exp2f(ml[s].x - M);
-    Lsum += ml[s].y * f;
-    acc += po[(int64_t)s * HD] * f;
+  for (int s = t; s < a.n_split; s += kCombineThreads) M = fmaxf(M, ml[s].x);
+  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  if ((t & 63) == 0) s_red[t >> 6] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  // weighted sums of this thread's key ranges
+  const float *po = a.part_o + head * a.n_split * HD + col * 4;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f}, lsum = 0.f;
+#pragma unroll 4
+  for (int s = grp; s < a.n_split; s += NG) {
+    const float2 p = ml[s];
+    const float f = __builtin_amdgcn_exp2f(p.x - M);
+    const float4 o4 = *(const float4 *)(po + (int64_t)s * HD);
+    lsum += p.y * f;
+    acc[0] += o4.x * f; acc[1] += o4.y * f; acc[2] += o4.z * f; acc[3] += o4.w * f;
   }
-  a.out[head * HD + threadIdx.x] = Lsum > 0.f ? acc / Lsum : 0.f;
-  if (a.lse != nullptr && threadIdx.x == 0)
-    a.lse[head] = Lsum > 0.f ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+#pragma unroll
+  for (int e = 0; e < 4; ++e) s_acc[grp][col * 4 + e] = acc[e];
+  if (col == 0) s_acc[grp][HD] = lsum;
+  __syncthreads();
+  if (t < HD) {
+    float v = 0.f, Lsum = 0.f;
+#pragma unroll
+    for (int g2 = 0; g2 < NG; ++g2) { v += s_acc[g2][t]; Lsum += s_acc[g2][HD]; }
+    a.out[head * HD + t] = Lsum > 0.f ? v / Lsum : 0.f;
+    if (a.lse != nullptr && t == 0)
+      a.lse[head] = Lsum > 0.f ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+  }
 }
 
 template <int DT, int HD>
@@ -265,7 +291,7 @@ int launch_decode_hd(const DecodeArgs &a, int batch_slice, int g, hipStream_t s)
   else if constexpr (DT != CHUNKKV_F32) hipLaunchKernelGGL((decode_kernel<DT, HD, 8>), grid, dim3(kThreads), 0, s, a);
   else return CHUNKKV_ERR_UNSUPPORTED;
   if (hipGetLastError() != hipSuccess) return CHUNKKV_ERR_LAUNCH;
-  hipLaunchKernelGGL((decode_combine_kernel<HD>), dim3(batch_slice * a.n_q_heads), dim3(HD), 0, s, a);
+  hipLaunchKernelGGL((decode_combine_kernel<HD>), dim3(batch_slice * a.n_q_heads), dim3(kCombineThreads), 0, s, a);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
