@@ -67,6 +67,7 @@ DECODE_CASES = {
     "bf16_g8_d64": small("llama8b_8k", n_q_heads=16, n_kv_heads=2, head_dim=64, seqlens=(3000,), n_spans=(5,)),
     "bf16_g16": small("llama8b_8k", n_q_heads=32, n_kv_heads=2, window=16, seqlens=(700,), n_spans=(4,)),
     "bf16_g3_nhd": small("llama8b_8k", n_q_heads=6, n_kv_heads=2, seqlens=(4100,), n_spans=(9,), layout="nhd"),
+    "bf16_b19_sliced": small("ragged_b8", seqlens=tuple(40 + 53 * i for i in range(19)), n_spans=(1,) * 19, n_layers=1),
     "f16_g4": small("llama8b_8k", dtype="f16", seqlens=(5000,), n_spans=(20,)),
     "f16_g8_d64": small("llama8b_8k", dtype="f16", n_q_heads=16, n_kv_heads=2, head_dim=64, seqlens=(1300,), n_spans=(5,)),
     "f32_tiny": small("tiny"),

@@ -241,6 +241,9 @@ STACK_CASES = {
     "bf16_4k_x5": (small("llama8b_32k_stack", seqlens=(4096,), n_spans=(20,), n_layers=5), [1, 2, 4, 7]),
     "ragged_x4": (small("ragged_b8", seqlens=(1500, 640, 2304), n_spans=(7, 3, 11), n_layers=4, chunk=5, keep_pct=30), [1, 3]),
     "w64_20pct_x2": (small("llama8b_128k_stack", seqlens=(3000,), n_spans=(9,), n_layers=2, keep_pct=20), [2]),
+    # more sequences and more layers than one launch carries as kernel arguments (16 and 32): the host slices
+    "sliced_b19_x35": (small("ragged_b8", seqlens=tuple(90 + 37 * i for i in range(19)), n_spans=(1,) * 19, n_layers=35,
+                             keep_pct=20), [1, 2]),
     "f16_4k_x4": (small("llama8b_128k_stack", dtype="f16", seqlens=(4096,), n_spans=(20,), n_layers=4), [1, 2]),
 }
 
