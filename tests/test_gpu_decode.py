@@ -211,3 +211,42 @@ def test_decode_128k_full_and_compressed_sampled_heads(lib):
         idx = orc.kept_token_indices(got[0][h][0], got[0][h][1], wl.seqlens[0], w, c)
         check_decode(out_c.cpu().numpy()[0, head:head + 1], lse_c.cpu().numpy()[0, head:head + 1], qb[head:head + 1],
                      k[h:h + 1, idx], v[h:h + 1, idx])
+
+
+def test_decode_call_replays_from_a_hip_graph(lib):
+    """A decoding loop captures the call once and replays it with new queries in the same buffers: kernels
+    only, no copies, memsets or allocations.  Every replay, with eager work in between, equals the eager call."""
+    wl = small("llama8b_8k", seqlens=(6000,), n_spans=(20,))
+    li = W.make_layer(wl, 0, DEV)
+    prob = H.make_problem(lib, wl, li)
+    Hq, d = wl.n_q_heads, wl.head_dim
+    ws = torch.empty(lib.chunkkv_decode_workspace_bytes(prob, False), dtype=torch.uint8, device=DEV)
+    q_buf = decode_query(li).clone()
+    out_g = torch.zeros((1, Hq, d), dtype=torch.float32, device=DEV)
+    lse_g = torch.zeros((1, Hq), dtype=torch.float32, device=DEV)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lib.chunkkv_decode_attention(prob, False, None, q_buf, li.k, li.v, out_g, lse_g, ws)   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            lib.chunkkv_decode_attention(prob, False, None, q_buf, li.k, li.v, out_g, lse_g, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    ws_e = torch.empty_like(ws)
+    for rep in range(3):
+        q_new = li.q[:, :, rep, :].contiguous()          # another window row as the "next token"
+        q_buf.copy_(q_new)
+        out_g.fill_(3.0)
+        lse_g.fill_(3.0)
+        ws.fill_(0xA5)                                    # the workspace is scratch: its contents never matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        out_e = torch.zeros_like(out_g)
+        lse_e = torch.zeros_like(lse_g)
+        lib.chunkkv_decode_attention(prob, False, None, q_new, li.k, li.v, out_e, lse_e, ws_e)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e) and torch.equal(lse_g, lse_e), rep
+    _, k, v = H.seq_arrays(wl, li, 0)
+    check_decode(out_g.cpu().numpy()[0], lse_g.cpu().numpy()[0], W.tensor_bits(q_buf[0]), k, v)
