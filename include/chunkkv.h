@@ -205,8 +205,8 @@ int chunkkv_set_single_pass(int32_t enable);
  * enqueues the gather of a set on an internal helper stream (created on first use, default priority,
  * ordered after `stream`'s prior work and joined back into it with events before the call returns) so
  * that it can run beside the scoring of the next set.  The default is 0: one set, everything on
- * `stream` (on MI355X the scoring kernels leave no register room for co-resident gather wavefronts and
- * every extra dependent launch costs tens of microseconds, so the split does not pay off).         */
+ * `stream` (on MI355X the split does not pay off: measured, scoring and gather that run side by side take as
+ * long as one after the other).  The setting changes the launch plan: query chunkkv_workspace_bytes after it. */
 int chunkkv_set_overlap(int32_t sets);
 
 /* Measurement aid (the per-kernel durations the roofline figures need; Algorithm 2's T_compress and

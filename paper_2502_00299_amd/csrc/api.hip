@@ -147,7 +147,7 @@ int decode_plan(const chunkkv_problem *p, bool compacted, DecodePlan *pl) {
   return CHUNKKV_OK;
 }
 
-// Workspace layout and key-range split; a pure function of (problem, n_layers, reuse).
+// Workspace layout and key-range split; a pure function of (problem, n_layers, reuse) and the overlap setting.
 int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   if (n_layers < 1 || reuse < 1) return CHUNKKV_ERR_SHAPE;
   const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
