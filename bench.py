@@ -375,6 +375,10 @@ def main():
         "roofline_mfma": mfma,
         "kernels_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in kern.items()},
         "decode_attention": decode_leg,
+        # Eq. 1 for this workload's geometry (kv-heads, not query heads, hold the cache under grouped-query attention)
+        "kv_cache_bytes": {"full": N * sum(2 * wl.n_kv_heads * L * wl.head_dim * wl.elem_bytes for L in wl.seqlens),
+                           "compressed": N * sum(2 * wl.n_kv_heads * (nk + wl.window) * wl.head_dim * wl.elem_bytes
+                                                 for nk in n_keep)},
         "with_caller_lse": lse_leg,
         "streaming_per_layer": stream_leg,
         "hip_graph_replay": graph_leg,

@@ -53,7 +53,9 @@ equal the plain scores, and a shift of the log-sum-exp scales them by exp(-shift
 the Jaccard similarity is pinned on hand-counted overlaps; decode attention
 is pinned on one token (returns its value row), identical keys (mean of the
 value rows), a dominant key, a library scaled-dot-product attention, explicit
-loops, a library logsumexp, and the rule that merges two partial results.
+loops, a library logsumexp, and the rule that merges two partial results;
+the cache-size formula reproduces the worked example printed beside Eq. 1
+(tests/golden/eq1_kv_cache_memory.json) and the reuse speed-up model its stated limit.
 The paper prints no worked numeric example of this path, so parity on real
 prompts is unpinned; everything above is pinned by mathematics only.
 """
@@ -255,6 +257,19 @@ def compact(k: np.ndarray, v: np.ndarray, sel_chunk: Sequence[np.ndarray], sel_l
         ko.append(k[h][idx])
         vo.append(v[h][idx])
     return np.stack(ko), np.stack(vo)
+
+
+def kv_cache_bytes(batch: int, seq_len: int, n_layers: int, n_heads: int, head_dim: int, bytes_per_value: int = 2) -> int:
+    """Memory of the KV cache in the decoding stage, Eq. 1: 2 (K and V) * B * S * L * N * D * bytes per value
+    (2 for float16)."""
+    return 2 * batch * seq_len * n_layers * n_heads * head_dim * bytes_per_value
+
+
+def reuse_speedup(n_layers: int, n_reuse: int, t_compress: float, t_select: float) -> float:
+    """Speed-up model of layer-wise index reuse (Appendix B.1.1): N*Tc over (N/R)*Tc + (N - N/R)*Ts, with
+    N/R taken as the real-valued quotient the formula prints."""
+    scored = n_layers / n_reuse
+    return n_layers * t_compress / (scored * t_compress + (n_layers - scored) * t_select)
 
 
 def decode_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[float] = None):

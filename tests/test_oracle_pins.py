@@ -497,3 +497,28 @@ def test_decode_widens_stored_16_bit_values_exactly():
     want16, _ = orc.decode_attention(qf.astype(np.float16).astype(np.float64), kf.astype(np.float16).astype(np.float64),
                                      vf.astype(np.float16).astype(np.float64))
     assert np.array_equal(got16, want16)
+
+
+# ------------------------------------------------------------------ sizing formulas the paper states
+def test_cache_size_formula_reproduces_the_papers_worked_example():
+    import json
+    import os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "eq1_kv_cache_memory.json")))
+    m = orc.kv_cache_bytes(**g["inputs"])
+    assert m == g["bytes"] == 2 ** 30                    # "nearly 1 GB": exactly 1 GiB
+    inp = dict(g["inputs"])
+    inp["batch"] = 24
+    assert orc.kv_cache_bytes(**inp) <= g["card_bytes"]  # 24 sequences still fit a 24 GiB card ...
+    inp["batch"] = 25
+    assert orc.kv_cache_bytes(**inp) > g["card_bytes"]   # ... "exceeds 24" does not
+    # linear in every factor
+    assert orc.kv_cache_bytes(2, 3, 5, 7, 11, 2) == 2 * 2 * 3 * 5 * 7 * 11 * 2
+
+
+def test_reuse_speedup_model_limits():
+    assert orc.reuse_speedup(32, 1, 3.0, 0.5) == 1.0                       # no reuse, no gain
+    assert math.isclose(orc.reuse_speedup(32, 2, 1.0, 0.0), 2.0)          # negligible gather time: about R
+    assert math.isclose(orc.reuse_speedup(32, 4, 1.0, 0.0), 4.0)
+    # a gather as expensive as a full compression gains nothing; in between the closed form by hand
+    assert math.isclose(orc.reuse_speedup(32, 2, 1.0, 1.0), 1.0)
+    assert math.isclose(orc.reuse_speedup(32, 2, 1.0, 0.287), 32 / (16 + 16 * 0.287))
