@@ -115,7 +115,7 @@ int check_problem(const chunkkv_problem *p, bool need_out) {
 bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }
 
 // Key-range split and workspace of the decode-attention call: a pure function of the problem.  About
-// kDecodeTargetWorkgroups workgroups per launch, never fewer than kDecodeMinRows rows per range.
+// kDecodeTargetWorkgroups working workgroups per launch, never fewer than kDecodeMinRows rows per range.
 constexpr int kDecodeTargetWorkgroups = 1024;
 constexpr int kDecodeMinRows = 256;
 struct DecodePlan {
@@ -123,21 +123,21 @@ struct DecodePlan {
   size_t off_ml, off_o, total;
 };
 int decode_plan(const chunkkv_problem *p, bool compacted, DecodePlan *pl) {
-  int64_t n_max = 1;
+  int64_t n_max = 1, n_sum = 0;
   for (int b = 0; b < p->batch; ++b) {
     const int64_t n = compacted ? (int64_t)p->n_keep[b] + p->window : p->seqlen[b];
     n_max = n > n_max ? n : n_max;
+    n_sum += n;
   }
   const int g = p->n_q_heads / p->n_kv_heads;
   const int G = decode_heads_per_wg(p->dtype, g), nz = (g + G - 1) / G;
-  const int nb = p->batch < kMaxBatchPerLaunch ? p->batch : kMaxBatchPerLaunch;
-  int64_t per_head = kDecodeTargetWorkgroups / ((int64_t)nb * p->n_kv_heads * nz);
-  per_head = per_head < 1 ? 1 : per_head;
-  const int64_t by_rows = (n_max + kDecodeMinRows - 1) / kDecodeMinRows;
-  int64_t n_split = per_head < by_rows ? per_head : by_rows;
-  int64_t rows = (n_max + n_split - 1) / n_split;
+  // every sequence is cut into ranges of the same length, chosen so that all sequences together give about
+  // kDecodeTargetWorkgroups workgroups with rows to read (short sequences then use only the first ranges of the grid)
+  const int64_t launches = (p->batch + kMaxBatchPerLaunch - 1) / kMaxBatchPerLaunch;
+  int64_t rows = (n_sum * p->n_kv_heads * nz / launches + kDecodeTargetWorkgroups - 1) / kDecodeTargetWorkgroups;
+  rows = rows < kDecodeMinRows ? kDecodeMinRows : rows;
   rows = (rows + 127) / 128 * 128;
-  n_split = (n_max + rows - 1) / rows;
+  const int64_t n_split = (n_max + rows - 1) / rows;
   pl->n_split = (int)n_split;
   pl->rows_per_split = (int)rows;
   const size_t heads = (size_t)p->batch * p->n_q_heads;

@@ -9,7 +9,16 @@
 // partial dot products with DPP adds (no LDS).  Each group of LPR lanes runs its own online softmax over the
 // rows it meets; the groups of a wavefront, the wavefronts of a workgroup and the key ranges of a head are
 // merged afterwards by the usual (max, sum, weighted output) rule, always in the same order.
+// With 16 lanes per row and 4 or 8 heads per workgroup the 4 x G partial dot products of a step are not
+// all-reduced but reduce-scattered: the lanes hold them in an order permuted by their own index (the rows
+// they load and the heads they keep in registers are XOR-swizzled), so each of the four halving steps is
+// one DPP add per kept value and lane (4u + jb) of a row group ends with the complete scores of row u for
+// heads jb*G/4 .. jb*G/4 + G/4 - 1.  That lane alone does the softmax arithmetic of those scores; the
+// weights reach the 16 lanes again as DPP row broadcasts feeding the value accumulation.
 // Grid: x = key range, y = (sequence, kv-head), z = batch of G query heads of the kv-head.
+#include <type_traits>
+#include <utility>
+
 #include "internal.h"
 
 namespace ckv {
@@ -36,6 +45,20 @@ __device__ __forceinline__ float row_sum(float x) {
   if constexpr (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror: the other half of 16 lanes
   if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
   return x;
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float x) {
+  return __builtin_amdgcn_update_dpp(0.f, x, CTRL, 0xf, 0xf, false);
+}
+// value of lane N of every row of 16 lanes
+template <int N>
+__device__ __forceinline__ float row_bcast(float x) {
+  return dpp_get<0x150 + N>(x);  // row_newbcast:N
+}
+template <int... I, typename F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F f) {
+  (f(std::integral_constant<int, I>{}), ...);
 }
 
 // 16 bytes of a row as fp32 values (8 for the 16-bit types, 4 for fp32)
@@ -115,13 +138,24 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeArgs a) {
   const char *vbase = (const char *)a.v + head_off + seg * 16;
   const int64_t tok = a.stride_tok * ESZ;
 
+  // reduce-scatter variant (see the file header): lane (4 * ub + jb) of a row group owns row ub, heads jb * NR ..
+  constexpr bool kScatter = LPR == 16 && U == 4 && (G == 4 || G == 8);
+  constexpr int LG = G == 8 ? 3 : 2;   // log2(G) where the variant applies
+  constexpr int NR = kScatter ? G / 4 : 1;
+  const int ub = kScatter ? (lane & 15) >> 2 : 0, jb = kScatter ? lane & 3 : 0;
+  const int jsw = jb << (LG - 2);      // register j holds head j ^ jsw
+
   u32x4 qreg[G];
 #pragma unroll
   for (int j = 0; j < G; ++j) {
+    const int jh = j ^ jsw;
     qreg[j] = u32x4{0, 0, 0, 0};
-    if (j0 + j < g)
-      qreg[j] = *(const u32x4 *)((const char *)a.q + ((int64_t)b * a.n_q_heads + (int64_t)h * g + j0 + j) * ROWB + seg * 16);
+    if (j0 + jh < g)
+      qreg[j] = *(const u32x4 *)((const char *)a.q + ((int64_t)b * a.n_q_heads + (int64_t)h * g + j0 + jh) * ROWB + seg * 16);
   }
+  float m_own[NR], l_own[NR];          // scatter variant: statistics of the heads this lane owns
+#pragma unroll
+  for (int x = 0; x < NR; ++x) { m_own[x] = kDecodeNegBig; l_own[x] = 0.f; }
   float m[G], l[G], o[G][EPL];
 #pragma unroll
   for (int j = 0; j < G; ++j) {
@@ -135,50 +169,121 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeArgs a) {
   // rows r0 .. r1-1; a step of the workgroup covers NW * U * RPW consecutive rows
   for (int base = r0 + wave * (U * RPW); base < r1; base += NW * U * RPW) {
     u32x4 kr[U], vr[U];
-    bool valid[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int row = base + u * RPW + grp;
-      valid[u] = row < r1;
-      const int64_t off = (int64_t)(valid[u] ? row : r1 - 1) * tok;  // r1 >= 1 inside the loop
-      kr[u] = *(const u32x4 *)(kbase + off);
-      vr[u] = *(const u32x4 *)(vbase + off);
+      const int rowv = base + u * RPW + grp;           // V: register u holds row u
+      const int rowk = base + (u ^ ub) * RPW + grp;    // K: register u holds row u ^ ub (ub = 0 without the swizzle)
+      kr[u] = *(const u32x4 *)(kbase + (int64_t)(rowk < r1 ? rowk : r1 - 1) * tok);  // r1 >= 1 inside the loop
+      vr[u] = *(const u32x4 *)(vbase + (int64_t)(rowv < r1 ? rowv : r1 - 1) * tok);
     }
-    float s[U][G];
+    if constexpr (kScatter) {
+      float x[U][G];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int j = 0; j < G; ++j) {
-        const float d = row_sum<LPR>(dot16<DT>(kr[u], qreg[j]));
-        s[u][j] = valid[u] ? d * c1 : -3.0e38f;
+        for (int jj = 0; jj < G; ++jj) x[u][jj] = dot16<DT>(kr[u], qreg[jj]);
+      // four halving steps; the partner lane differs in bit 3 / bits 0-2 / bit 1 / bit 0 of the lane index
+      constexpr int J3 = 3 << (LG - 2);
+      float y[2][G], z[G], t[G / 2], r[NR];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int jj = 0; jj < G; ++jj) y[u][jj] = x[u][jj] + dpp_get<0x128>(x[u ^ 2][jj]);   // row_ror:8
+#pragma unroll
+      for (int jj = 0; jj < G; ++jj) z[jj] = y[0][jj] + dpp_get<0x141>(y[1][jj ^ J3]);        // row_half_mirror
+#pragma unroll
+      for (int jj = 0; jj < G / 2; ++jj) t[jj] = z[jj] + dpp_get<0x4E>(z[jj ^ (G / 2)]);      // quad_perm [2,3,0,1]
+#pragma unroll
+      for (int jj = 0; jj < NR; ++jj) r[jj] = t[jj] + dpp_get<0xB1>(t[jj ^ (G / 4)]);         // quad_perm [1,0,3,2]
+      // r[x]: row ub of the step, head jb * NR + x.  Softmax statistics per head: maximum over the four rows,
+      // which sit in the lanes 4, 8 and 12 further on.
+      const bool valid_own = base + ub * RPW + grp < r1;
+      float p[NR];
+#pragma unroll
+      for (int xx = 0; xx < NR; ++xx) {
+        const float sc = valid_own ? r[xx] * c1 : -3.0e38f;
+        float smax = fmaxf(sc, dpp_get<0x128>(sc));
+        smax = fmaxf(smax, dpp_get<0x124>(smax));   // row_ror:4; the value is already the same 8 lanes apart
+        if (__builtin_amdgcn_ballot_w64(smax > m_own[xx]) != 0) {
+          const float m_new = fmaxf(m_own[xx], smax);
+          const float f = __builtin_amdgcn_exp2f(m_own[xx] - m_new);
+          l_own[xx] *= f;
+          m_own[xx] = m_new;
+          // the outputs of head jbp * NR + xx live in all 16 lanes: its factor comes from lane jbp
+          static_for(std::make_integer_sequence<int, 4>{}, [&](auto jbp_c) __attribute__((always_inline)) {
+            constexpr int JBP = decltype(jbp_c)::value;
+            const float fb = row_bcast<JBP>(f);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[JBP * NR + xx][e] *= fb;
+          });
+        }
+        p[xx] = __builtin_amdgcn_exp2f(sc - m_own[xx]);
+        l_own[xx] += p[xx];
+      }
+      static_for(std::make_integer_sequence<int, U>{}, [&](auto u_c) __attribute__((always_inline)) {
+        constexpr int UU = decltype(u_c)::value;
+        float vf[EPL];
+        widen16<DT>(vr[UU], vf);
+        static_for(std::make_integer_sequence<int, G>{}, [&](auto j_c) __attribute__((always_inline)) {
+          constexpr int JJ = decltype(j_c)::value;
+          const float pb = row_bcast<4 * UU + JJ / NR>(p[JJ % NR]);   // weight of (row UU, head JJ)
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) o[JJ][e] = __builtin_fmaf(pb, vf[e], o[JJ][e]);
+        });
+      });
+    } else {
+      float s[U][G];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const bool valid = base + u * RPW + grp < r1;
+#pragma unroll
+        for (int jj = 0; jj < G; ++jj) {
+          const float d = row_sum<LPR>(dot16<DT>(kr[u], qreg[jj]));
+          s[u][jj] = valid ? d * c1 : -3.0e38f;
+        }
       }
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-      float smax = s[0][j];
+      for (int jj = 0; jj < G; ++jj) {
+        float smax = s[0][jj];
 #pragma unroll
-      for (int u = 1; u < U; ++u) smax = fmaxf(smax, s[u][j]);
-      if (__builtin_amdgcn_ballot_w64(smax > m[j]) != 0) {
-        const float m_new = fmaxf(m[j], smax);
-        const float f = __builtin_amdgcn_exp2f(m[j] - m_new);
-        l[j] *= f;
+        for (int u = 1; u < U; ++u) smax = fmaxf(smax, s[u][jj]);
+        if (__builtin_amdgcn_ballot_w64(smax > m[jj]) != 0) {
+          const float m_new = fmaxf(m[jj], smax);
+          const float f = __builtin_amdgcn_exp2f(m[jj] - m_new);
+          l[jj] *= f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[j][e] *= f;
-        m[j] = m_new;
+          for (int e = 0; e < EPL; ++e) o[jj][e] *= f;
+          m[jj] = m_new;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) s[u][jj] = __builtin_amdgcn_exp2f(s[u][jj] - m[jj]);  // now the weight p
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) s[u][j] = __builtin_amdgcn_exp2f(s[u][j] - m[j]);  // now the weight p
-    }
+      for (int u = 0; u < U; ++u) {
+        float vf[EPL];
+        widen16<DT>(vr[u], vf);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float vf[EPL];
-      widen16<DT>(vr[u], vf);
+        for (int jj = 0; jj < G; ++jj) {
+          l[jj] += s[u][jj];
 #pragma unroll
-      for (int j = 0; j < G; ++j) {
-        l[j] += s[u][j];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) o[j][e] = __builtin_fmaf(s[u][j], vf[e], o[j][e]);
+          for (int e = 0; e < EPL; ++e) o[jj][e] = __builtin_fmaf(s[u][jj], vf[e], o[jj][e]);
+        }
       }
     }
+  }
+  if constexpr (kScatter) {
+    // back to the replicated form the merges below expect: every lane learns (m, l) of every head
+    float lsum[NR];
+#pragma unroll
+    for (int xx = 0; xx < NR; ++xx) {
+      lsum[xx] = l_own[xx] + dpp_get<0x128>(l_own[xx]);
+      lsum[xx] += dpp_get<0x124>(lsum[xx]);
+    }
+    static_for(std::make_integer_sequence<int, G>{}, [&](auto j_c) __attribute__((always_inline)) {
+      constexpr int JJ = decltype(j_c)::value;
+      m[JJ] = row_bcast<JJ / NR>(m_own[JJ % NR]);
+      l[JJ] = row_bcast<JJ / NR>(lsum[JJ % NR]);
+    });
   }
 
   // merge the row groups of the wavefront (lanes that hold the same 16 bytes of the row)

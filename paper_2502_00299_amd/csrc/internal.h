@@ -104,7 +104,7 @@ struct DecodeArgs {
 
 // query heads of one kv-head that a decode workgroup serves: 1, 2, 4 or 8 (fp32 caches: at most 4, registers)
 inline int decode_heads_per_wg(int dtype, int g) {
-  const int G = g >= 8 ? 8 : (g > 2 ? 4 : g);
+  const int G = g > 4 ? 8 : (g > 2 ? 4 : g);  // 5..7 heads: one padded batch of 8, not two passes over K and V
   return dtype == CHUNKKV_F32 && G > 4 ? 4 : G;
 }
 
