@@ -350,7 +350,23 @@ def main():
                 _, kt_d = timed(run_decode, args.steps, 1, with_kernel_timing=True)
                 nbytes = N * sum(2 * wl.n_kv_heads * t * wl.head_dim * wl.elem_bytes for t in toks)
                 t_k, n_k = kt_d["decode"]
-                legs[name] = {"ms_per_token_all_layers": ms_d, "kernel_ms_per_layer": t_k / max(n_k, 1),
+                ms_g = None
+                try:   # the same N calls replayed from a HIP graph, as a captured decoding loop would issue them
+                    side = torch.cuda.Stream()
+                    side.wait_stream(torch.cuda.current_stream())
+                    graph_d = torch.cuda.CUDAGraph()
+                    with torch.cuda.stream(side):
+                        run_decode()
+                        side.synchronize()
+                        with torch.cuda.graph(graph_d, stream=side):
+                            run_decode()
+                    torch.cuda.current_stream().wait_stream(side)
+                    ms_g, _ = timed(graph_d.replay, args.steps, args.warmup)
+                    del graph_d
+                except Exception as e:
+                    log(f"decode graph replay failed: {e!r}")
+                legs[name] = {"ms_per_token_all_layers": ms_d, "ms_from_hip_graph": ms_g,
+                              "kernel_ms_per_layer": t_k / max(n_k, 1),
                               "algorithmic_bytes": nbytes, "achieved_GBps": nbytes / (ms_d * 1e-3) / 1e9,
                               "kernel_GBps": nbytes / N / (t_k / max(n_k, 1) * 1e-3) / 1e9,
                               "hbm_frac": nbytes / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBPS}
