@@ -65,6 +65,8 @@ DECODE_CASES = {
     "bf16_g2_d64": small("llama8b_8k", n_q_heads=4, n_kv_heads=2, head_dim=64, seqlens=(1531,), n_spans=(5,)),
     "bf16_g7_ragged": small("ragged_b8", seqlens=(2049, 517, 33), n_spans=(10, 2, 0), n_layers=1),
     "bf16_g8_d64": small("llama8b_8k", n_q_heads=16, n_kv_heads=2, head_dim=64, seqlens=(3000,), n_spans=(5,)),
+    "bf16_g5": small("llama8b_8k", n_q_heads=10, n_kv_heads=2, seqlens=(1777,), n_spans=(5,)),
+    "f16_g6": small("llama8b_8k", dtype="f16", n_q_heads=12, n_kv_heads=2, seqlens=(2222,), n_spans=(5,)),
     "bf16_g16": small("llama8b_8k", n_q_heads=32, n_kv_heads=2, window=16, seqlens=(700,), n_spans=(4,)),
     "bf16_g3_nhd": small("llama8b_8k", n_q_heads=6, n_kv_heads=2, seqlens=(4100,), n_spans=(9,), layout="nhd"),
     "bf16_b19_sliced": small("ragged_b8", seqlens=tuple(40 + 53 * i for i in range(19)), n_spans=(1,) * 19, n_layers=1),
