@@ -83,8 +83,14 @@ def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers, gpu_sel=None):
             orc.compact(k, v, [x[0] for x in sel], [x[1] for x in sel], wl.window, wl.chunk)
     dt = time.perf_counter() - t0
     est_stack = dt * wl.n_layers / n_sample_layers
+    cpu = None
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), None)
+    except OSError:
+        pass
     out = {"value": sum(wl.seqlens) / est_stack, "unit": "prefix tokens/s", "cores": int(threads),
-           "kind": "oracle",
+           "kind": "oracle", "cpu": cpu,
            "sample": f"layers 0..{n_sample_layers - 1} of {wl.n_layers} (all sequences and kv-heads) in "
                      f"{dt:.1f} s, scaled by {wl.n_layers}/{n_sample_layers}"}
     if gpu_sel is not None:
