@@ -228,6 +228,15 @@ def main():
     # per-kernel durations: a second loop of the same steps with a HIP event pair around every launch
     # (kept out of the headline loop: the event packets add gaps between the kernels)
     _, kt = timed(run_main, args.steps, 1, with_kernel_timing=True)
+    # spread of single steps: one HIP-event pair per step on the launch stream (outside the headline loop)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.steps, 20))]
+    for e0, e1 in evs:
+        e0.record()
+        run_main()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    step_spread = {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1], "n": len(per_step)}
     tokens = sum(wl.seqlens)
     value = tokens / (ms * 1e-3)
     ab = algorithmic_bytes(wl, n_keep, N, R)
@@ -385,7 +394,7 @@ def main():
     out = {
         "metric": "prefix tokens compressed/sec (32-layer stack) + achieved HBM GB/s vs peak",
         "value": value, "unit": "prefix tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "ms_per_step": ms, "step_ms_hip_events": step_spread, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {N} layers, B={wl.batch}, L={list(wl.seqlens)}, Hq={wl.n_q_heads}, "
                                f"Hkv={wl.n_kv_heads}, d={wl.head_dim}, w={wl.window}, c={wl.chunk}, "
