@@ -191,6 +191,22 @@ int chunkkv_decode_attention(const chunkkv_problem *prob, int32_t compacted, con
                              const void *k, const void *v, float *out, float *lse, void *workspace,
                              size_t workspace_bytes, void *stream);
 
+/* chunkkv_decode_attention for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and
+ * errors as chunkkv_decode_attention, without the workspace: the partial results of the key ranges live in a
+ * device-resident array of CHUNKKV_STATIC_SCRATCH_BYTES that is part of the library image (every GPU the
+ * library runs on holds it until the process ends).  The call allocates nothing and frees nothing.
+ *   - a problem whose chunkkv_decode_workspace_bytes() exceeds CHUNKKV_STATIC_SCRATCH_BYTES is refused with
+ *     CHUNKKV_ERR_WORKSPACE and nothing is enqueued (8 MiB covers 32 query heads over a 128K-token cache and
+ *     8 sequences x 28 query heads of up to 64K tokens);
+ *   - all calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *     threads) race on it; calls on one stream are ordered and safe;
+ *   - the first call on a device looks up the array's device address (no allocation).                      */
+#define CHUNKKV_STATIC_SCRATCH_BYTES (8u << 20)
+int chunkkv_decode_attention_static(const chunkkv_problem *prob, int32_t compacted, const int32_t *kv_len,
+                                    const void *q, const void *k, const void *v, float *out, float *lse,
+                                    void *stream);
+
 /* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 and fp16 caches,
  * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
  * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a

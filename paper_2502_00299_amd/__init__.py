@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     chunkkv_compress_stack,
     chunkkv_compress_stack_lse,
     chunkkv_decode_attention,
+    chunkkv_decode_attention_static,
     chunkkv_decode_workspace_bytes,
     chunkkv_jaccard,
     chunkkv_score,

@@ -21,6 +21,7 @@ F32, BF16, F16 = 0, 1, 2
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
            "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_decode_workspace_bytes", "chunkkv_decode_attention",
+           "chunkkv_decode_attention_static",
            "chunkkv_set_overlap", "chunkkv_set_single_pass",
            "chunkkv_set_whole_chunks",
            "chunkkv_timing_begin",
@@ -158,6 +159,8 @@ def load_library(path: Optional[str] = None):
     lib.chunkkv_decode_attention.restype = C.c_int
     lib.chunkkv_decode_attention.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, vp, vp, vp, f32p, f32p, vp,
                                              C.c_size_t, vp]
+    lib.chunkkv_decode_attention_static.restype = C.c_int
+    lib.chunkkv_decode_attention_static.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, vp, vp, vp, f32p, f32p, vp]
     _lib = lib
     return lib
 
@@ -273,6 +276,13 @@ def chunkkv_decode_attention(prob: Problem, compacted: bool, kv_len, q, k, v, ou
         C.byref(cp), 1 if compacted else 0, _ptr(kv_len), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
         _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
         "chunkkv_decode_attention")
+
+
+def chunkkv_decode_attention_static(prob: Problem, compacted: bool, kv_len, q, k, v, out, lse, stream=None) -> None:
+    cp = prob.as_c()
+    _check(load_library().chunkkv_decode_attention_static(
+        C.byref(cp), 1 if compacted else 0, _ptr(kv_len), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
+        _stream(stream)), "chunkkv_decode_attention_static")
 
 
 def chunkkv_set_single_pass(enable: bool) -> None:

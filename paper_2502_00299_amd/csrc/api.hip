@@ -2,6 +2,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "internal.h"
 
 namespace ckv {
@@ -71,6 +73,32 @@ Overlap *overlap_state() {  // created on first use; default priority; lives unt
     return o;
   }();
   return st;
+}
+
+// ---- device-resident scratch for chunkkv_decode_attention_static ---------------------------------
+// One array per GPU the library runs on, held until the process ends.  Its name is only a host-side
+// stand-in: the device address is looked up once per device and kept; host code uses that pointer.
+constexpr size_t kStaticScratchBytes = CHUNKKV_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace
+}  // namespace ckv
+static __device__ __align__(256) unsigned char scratch[ckv::kStaticScratchBytes];
+namespace ckv {
+namespace {
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+// device address of `scratch` on the current device (looked up on the first call per device)
+int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CHUNKKV_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return CHUNKKV_ERR_LAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CHUNKKV_OK;
 }
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -612,6 +640,22 @@ int chunkkv_decode_attention(const chunkkv_problem *prob, int32_t compacted, con
     if (rc) return rc;
   }
   return CHUNKKV_OK;
+}
+
+int chunkkv_decode_attention_static(const chunkkv_problem *prob, int32_t compacted, const int32_t *kv_len,
+                                    const void *q, const void *k, const void *v, float *out, float *lse,
+                                    void *stream) {
+  // the size check comes first: a problem that does not fit is refused before anything else happens
+  int rc = check_problem(prob, compacted != 0);
+  if (rc) return rc;
+  DecodePlan pl;
+  if ((rc = decode_plan(prob, compacted != 0, &pl))) return rc;
+  if (pl.total > kStaticScratchBytes) return CHUNKKV_ERR_WORKSPACE;
+  void *ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  // every partial result the merge kernel reads is written by the range kernel of the same call, so nothing
+  // in the array has to be cleared between calls
+  return chunkkv_decode_attention(prob, compacted, kv_len, q, k, v, out, lse, ws, pl.total, stream);
 }
 
 int chunkkv_set_whole_chunks(int32_t enable) {
