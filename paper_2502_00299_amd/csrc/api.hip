@@ -9,9 +9,9 @@
 namespace ckv {
 namespace {
 
-constexpr int kFusedTableLimit = 16384;  // bytes of LDS the single-pass kernel keeps for indicator fragments (2 KB per phase)
 constexpr int kTargetWorkgroups = 4096;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
-constexpr int kTargetWorkgroupsFused = 4096;  // single-pass kernel: finer ranges balance ragged batches, same speed on one long sequence
+constexpr int kTargetWorkgroupsSingle = 4096;  // single-pass kernel: finer ranges balance ragged batches, same speed on one long sequence
+constexpr int kSinglePeriodKeys = 160;   // granule of the single-pass kernel's key ranges
 // Key tiles (16 KB) one scoring launch set should hold.  Measured on MI355X: every extra dependent launch
 // costs ~30 us of idle GPU, more than splitting the stack into sets wins back, so one set it is.
 constexpr int64_t kTilesPerLaunch = 1 << 30;
@@ -23,7 +23,7 @@ struct Plan {
   int tpw0, tpw1, max_split0;
   int fuse_chunks;
   // single-pass path: usable for this problem?  geometry and workspace
-  int fused_ok, period_keys, unit_keys, n_periods, tpw_f, max_split_f;
+  int single_ok, rows_pad_s, n_periods, tpw_s, max_split_s;
   size_t off_part, off_refs, off_scores, off_seloff, off_imp, off_ebuf, off_mper, total;
 };
 
@@ -210,58 +210,52 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
     const int s = ceil_div(ceil_div(p->seqlen[b], TK), pl->tpw0);
     if (s > pl->max_split0) pl->max_split0 = s;
   }
-  // single-pass path (bf16 or fp16, >= 65 window rows per kv-head, chunk pattern that fits the indicator table)
-  {
-    int gcd = 32, x = p->chunk;
-    while (x) { const int t = gcd % x; gcd = x; x = t; }
-    const int64_t pk = 32 / gcd * (int64_t)p->chunk;  // lcm(32, c)
-    const int64_t nslots = pk / p->chunk, phases = pk / 32;
-    pl->fused_ok = p->dtype != CHUNKKV_F32 && pl->geom.wq == 4 && nslots <= 16 &&
-                   phases * 2048 <= kFusedTableLimit;
-    pl->period_keys = pl->unit_keys = pl->n_periods = 0;
-    pl->tpw_f = pl->max_split_f = 1;
-    if (pl->fused_ok) {
-      int g2 = TK, y = (int)pk;
-      while (y) { const int t = g2 % y; g2 = y; y = t; }
-      pl->period_keys = (int)pk;
-      pl->unit_keys = (int)(pk / g2 * TK);  // lcm(TK, pk)
-      int64_t units = 0;
-      for (int b = 0; b < p->batch; ++b) {
-        units += ceil_div(p->seqlen[b], pl->unit_keys);
-        const int np = ceil_div(p->seqlen[b], pl->period_keys);
-        if (np > pl->n_periods) pl->n_periods = np;
-      }
-      // the kernels address E of one problem, and K of one (sequence, kv-head), with 32-bit byte offsets
-      if ((int64_t)pl->n_periods * pl->rows_pad * 48 >= (int64_t)1 << 32) pl->fused_ok = 0;
-
-      // key-range length in units: at most kTargetWorkgroupsFused workgroups, and ranges of at least 8 units
-      // (40 tiles at c = 10, so that a workgroup's start-up stays small) unless that would leave fewer
-      // workgroups than the chip holds at once (512)
-      const int64_t total_units = units * heads;
-      int64_t floor_units = (total_units + 511) / 512;
-      if (floor_units > 8) floor_units = 8;
-      pl->tpw_f = (int)((total_units + kTargetWorkgroupsFused - 1) / kTargetWorkgroupsFused);
-      if (pl->tpw_f < floor_units) pl->tpw_f = (int)floor_units;
-      if (pl->tpw_f < 1) pl->tpw_f = 1;
-      for (int b = 0; b < p->batch; ++b) {
-        const int sp = ceil_div(ceil_div(p->seqlen[b], pl->unit_keys), pl->tpw_f);
-        if (sp > pl->max_split_f) pl->max_split_f = sp;
-      }
+  // single-pass path
+  pl->single_ok = single_pass_ok(p->dtype, p->head_dim, rows, p->chunk) ? 1 : 0;
+  pl->rows_pad_s = rows > 128 ? 256 : 128;
+  pl->n_periods = 0;
+  pl->tpw_s = pl->max_split_s = 1;
+  if (pl->single_ok) {
+    int64_t periods = 0;
+    for (int b = 0; b < p->batch; ++b) {
+      const int np = ceil_div(p->seqlen[b], kSinglePeriodKeys);
+      periods += np;
+      if (np > pl->n_periods) pl->n_periods = np;
+    }
+    // the kernels address E of one problem with 32-bit byte offsets
+    if ((int64_t)pl->n_periods * pl->rows_pad_s * 96 >= (int64_t)1 << 32) pl->single_ok = 0;
+    // key-range length in periods: at most kTargetWorkgroupsSingle workgroups, and ranges of at least 16 periods
+    // (so that a workgroup's start-up stays small) unless that would leave fewer workgroups than the chip
+    // holds at once (512)
+    const int64_t total = periods * heads;
+    int64_t floor_p = (total + 511) / 512;
+    if (floor_p > 16) floor_p = 16;
+    pl->tpw_s = (int)((total + kTargetWorkgroupsSingle - 1) / kTargetWorkgroupsSingle);
+    if (pl->tpw_s < floor_p) pl->tpw_s = (int)floor_p;
+    if (pl->tpw_s < 1) pl->tpw_s = 1;
+    for (int b = 0; b < p->batch; ++b) {
+      const int sp = ceil_div(ceil_div(p->seqlen[b], kSinglePeriodKeys), pl->tpw_s);
+      if (sp > pl->max_split_s) pl->max_split_s = sp;
     }
   }
   const size_t problems = (size_t)pl->n_leaders * p->batch * p->n_kv_heads;
-  const int max_split_any = pl->max_split0 > pl->max_split_f ? pl->max_split0 : pl->max_split_f;
+  size_t part_bytes = problems * pl->max_split0 * pl->rows_pad * sizeof(float2);
+  if (pl->single_ok) {
+    const size_t pb = problems * pl->max_split_s * pl->rows_pad_s * 2 * sizeof(float2);
+    part_bytes = pb > part_bytes ? pb : part_bytes;
+  }
   size_t off = 0;
-  pl->off_part = off;   off += align256(problems * max_split_any * pl->rows_pad * sizeof(float2));
+  pl->off_part = off;   off += align256(part_bytes);
   pl->off_refs = off;   off += align256(problems * pl->rows_pad * sizeof(float));
   pl->off_scores = off; off += align256(problems * (size_t)p->score_cap * sizeof(float));
   pl->off_seloff = off; off += align256(problems * (size_t)p->sel_cap * sizeof(int32_t));
   pl->off_imp = off;
   if (!pl->fuse_chunks) off += align256(problems * (size_t)p->score_cap * p->chunk * sizeof(float));
   pl->off_ebuf = pl->off_mper = off;
-  if (pl->fused_ok) {
-    pl->off_ebuf = off; off += align256(problems * (size_t)pl->n_periods * pl->rows_pad * 48);  // 16 slots x 3 bytes
-    pl->off_mper = off; off += align256(problems * (size_t)pl->n_periods * pl->rows_pad * sizeof(float));
+  if (pl->single_ok) {
+    const size_t cells = problems * (size_t)pl->n_periods * pl->rows_pad_s * 2;   // (period, row, lane half)
+    pl->off_ebuf = off; off += align256(cells * (size_t)(3 * (80 / p->chunk)));
+    pl->off_mper = off; off += align256(cells * sizeof(float));
   }
   pl->total = off < 256 ? 256 : off;
   return CHUNKKV_OK;
@@ -319,23 +313,23 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
       la.n_q_heads = p->n_q_heads; la.n_kv_heads = p->n_kv_heads; la.window = p->window; la.rows_pad = pl.rows_pad;
       { Timed t(kCombine, s); rc = launch_lse_refs(la, ng, nb, s); }
       if (rc) return rc;
-    } else if (pl.fused_ok && g_single_pass && !token_imp) {
-      // one pass over K: per-(chunk, row) sums + running maxima, merge of the range statistics, weighted row sum
-      a.period_keys = pl.period_keys; a.unit_keys = pl.unit_keys; a.n_periods = pl.n_periods;
-      a.e_buf = (float *)(ws + pl.off_ebuf);
+    } else if (pl.single_ok && g_single_pass && !token_imp) {
+      // one pass over K: per-(chunk, row) sums and the references they are relative to; then the merge of the
+      // range statistics and the weighted row sum in one small kernel
+      a.n_periods = pl.n_periods;
+      a.e_buf = ws + pl.off_ebuf;
       a.m_period = (float *)(ws + pl.off_mper);
-      a.max_split = pl.max_split_f;
-      a.tiles_per_wg = pl.tpw_f;
-      int splitf = 1;
+      a.max_split = pl.max_split_s;
+      a.tiles_per_wg = pl.tpw_s;
+      a.rows_pad = pl.rows_pad_s;
+      int splits = 1;
       for (int i = 0; i < nb; ++i) {
-        const int sp = ceil_div(ceil_div(a.seq.seqlen[i], pl.unit_keys), pl.tpw_f);
-        splitf = sp > splitf ? sp : splitf;
+        const int sp = ceil_div(ceil_div(a.seq.seqlen[i], kSinglePeriodKeys), pl.tpw_s);
+        splits = sp > splits ? sp : splits;
       }
-      { Timed t(kStats, s); rc = launch_score_fused(p->dtype, p->head_dim, pl.geom, a, dim3(splitf, nb * p->n_kv_heads, ng), s); }
+      { Timed t(kStats, s); rc = launch_score_single(p->dtype, a, dim3(splits, nb * p->n_kv_heads, ng), s); }
       if (rc) return rc;
-      { Timed t(kCombine, s); rc = launch_stats_combine(a, ng, nb, pl.unit_keys, s); }
-      if (rc) return rc;
-      { Timed t(kColsum, s); rc = launch_fused_scores(a, ng, nb, s); }
+      { Timed t(kColsum, s); rc = launch_single_scores(a, ng, nb, s); }
       if (rc) return rc;
       continue;
     }

@@ -45,12 +45,11 @@ struct ScoreArgs {
   float *token_imp;        // [leader][batch_total][Hkv][imp_pitch] or null
   int64_t imp_pitch;
   int32_t fuse_chunks;     // pass 1: 1 = super-tiles hold whole chunks and chunk sums are written
-  // single-pass path (score_fused.h)
-  int32_t period_keys;     // lcm(32, c): keys after which the key-block / chunk pattern repeats
-  int32_t unit_keys;       // lcm(tile keys, period_keys): granule of the key-range split
-  int32_t n_periods;       // pitch of m_period: max over sequences of ceil(L / period_keys)
-  float *e_buf;            // [problem][n_periods][rows_pad] x 48 bytes: per-(chunk slot, row) sums of e, 24-bit floats
-  float *m_period;         // [problem][n_periods][rows_pad]  maximum those sums are relative to
+  // single-pass path (score_single.h): key ranges are whole periods of 160 keys (tiles_per_wg counts periods)
+  int32_t n_periods;       // pitch of e_buf / m_period: max over sequences of ceil(L / 160)
+  void *e_buf;             // [problem][n_periods][rows_pad][2 lane halves][80 / c] x 3 bytes: per-(chunk, row) sums of e
+  float *m_period;         // [problem][n_periods][rows_pad][2]  reference those sums are relative to
+                           // part_stats is [problem][max_split][rows_pad][2] on this path
 };
 
 // Caller-supplied row log-sum-exps -> row references of the importance pass.
@@ -136,11 +135,12 @@ int launch_score_pass(int pass, int dtype, int head_dim, const ScoreGeom &g, con
 int launch_stats_combine(const ScoreArgs &a, int n_leaders_slice, int batch_slice, int tile_keys,
                          hipStream_t s);
 int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
-int launch_score_fused(int dtype, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_score_single(int dtype, const ScoreArgs &a, dim3 grid, hipStream_t s);
 int launch_jaccard(const int32_t *sel_chunk, const int32_t *sel_len, const int32_t *sel_count, int sel_cap, int chunk,
                    int rows_per_group, int n_pairs, float *out, hipStream_t s);
 int launch_lse_refs(const LseArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
-int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
+int launch_single_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s);
+bool single_pass_ok(int dtype, int head_dim, int rows, int chunk);
 int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s);
 int launch_decode(int dtype, int head_dim, const DecodeArgs &a, int batch_slice, hipStream_t s);
 int launch_compact(int row_bytes, const CompactArgs &a, int n_layers_slice, int batch_slice,

@@ -7,8 +7,8 @@ namespace ckv {
 int launch_score_bf16(int pass, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
 int launch_score_f16(int pass, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
 int launch_score_f32(int pass, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
-int launch_score_fused_bf16(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
-int launch_score_fused_f16(int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_score_single_bf16(const ScoreArgs &a, dim3 grid, hipStream_t s);
+int launch_score_single_f16(const ScoreArgs &a, dim3 grid, hipStream_t s);
 
 bool score_geometry(int dtype, int head_dim, int rows, ScoreGeom *g) {
   if (dtype != CHUNKKV_F32 && dtype != CHUNKKV_BF16 && dtype != CHUNKKV_F16) return false;
@@ -34,10 +34,17 @@ int launch_score_pass(int pass, int dtype, int head_dim, const ScoreGeom &g, con
   return launch_score_f32(pass, head_dim, g, a, grid, s);
 }
 
-int launch_score_fused(int dtype, int head_dim, const ScoreGeom &g, const ScoreArgs &a, dim3 grid, hipStream_t s) {
+// Does the single-pass kernel take this problem?  16-bit caches of head_dim 128, 65 to 256 window rows per
+// kv-head, chunk sizes that cut a lane half's 80 keys into a multiple of four chunks.
+bool single_pass_ok(int dtype, int head_dim, int rows, int chunk) {
+  return (dtype == CHUNKKV_BF16 || dtype == CHUNKKV_F16) && head_dim == 128 && rows > 64 && rows <= 256 &&
+         (chunk == 5 || chunk == 10 || chunk == 20);
+}
+
+int launch_score_single(int dtype, const ScoreArgs &a, dim3 grid, hipStream_t s) {
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return CHUNKKV_OK;
-  if (dtype == CHUNKKV_BF16) return launch_score_fused_bf16(head_dim, g, a, grid, s);
-  if (dtype == CHUNKKV_F16) return launch_score_fused_f16(head_dim, g, a, grid, s);
+  if (dtype == CHUNKKV_BF16) return launch_score_single_bf16(a, grid, s);
+  if (dtype == CHUNKKV_F16) return launch_score_single_f16(a, grid, s);
   return CHUNKKV_ERR_UNSUPPORTED;
 }
 
@@ -132,84 +139,96 @@ int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, 
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
-// Single-pass path, last step: score[chunk] = sum over rows of E[chunk][row] * exp2(m_period[row] - ref[row]).
-// A workgroup of 256 threads takes kPeriodsPerGroup consecutive periods of one problem.  The E block of a
-// period is rows_pad x 48 bytes, contiguous: per row the 8 values of lane half 0 (chunk slots 0..3, 8..11)
-// and the 8 of half 1 (slots 4..7, 12..15), each value the upper three bytes of an fp32.  Thread t reads
-// the 12-byte pieces t, t + 256, ... (row t/4 + 64*i, quarter t%4 = four consecutive slots), so a load
-// instruction of a wavefront covers 768 contiguous bytes.  The four partial sums of a thread are reduced
-// over the threads of equal t%4, in a fixed order.
+// Single-pass path, second kernel: the row references and the chunk scores.
+//   ref_r = m_r + log2(sum_r), merged from the (reference, sum) pairs every key range and lane half of row r left
+//           (pairs merge associatively; always in the same order: range by range, lane half 0 first);
+//   score[chunk] = sum over rows of E[chunk][row] * exp2(m[chunk][row] - ref[row]).
+// A workgroup of 256 threads merges the statistics of its problem (one row per thread) and then takes
+// kPeriodsPerGroup consecutive periods.  Per period the scoring kernel left, for each lane half h and each
+// group ("part") of four consecutive chunks of that half, rows_pad pieces of 12 bytes (four sums, each the upper
+// three bytes of an fp32), and per lane half rows_pad references.  A wavefront takes one (period, half, part)
+// at a time: its lanes walk the rows (a load instruction covers 768 contiguous bytes), weigh, and the four
+// sums are reduced over the lanes in a fixed order.  The chunk of (half h, part p, j) is 2 (4 p + j) + h of the
+// period's 2 S chunks.  Rows past the real ones are skipped: nothing was written for them.
 // grid: x = period group, y = (sequence, kv-head), z = leader.
-constexpr int kPeriodsPerGroup = 8;
-constexpr int kMaxRowPasses = kMaxRows / 64;
-constexpr int kEBytesPerRowMisc = 48;  // as written by the single-pass scoring kernel
+constexpr int kPeriodsPerGroup = 32;
+constexpr int kSinglePeriod = 160, kSingleHalf = 80;   // as in the single-pass scoring kernel
 
-__global__ __launch_bounds__(256) void fused_scores_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(256) void single_scores_kernel(ScoreArgs a) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bl = blockIdx.y / a.n_kv_heads, h = blockIdx.y % a.n_kv_heads, z = blockIdx.z;
   const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
-  const int P = pick(a.seq.seqlen, bl) - a.window, c = a.chunk;
-  const int C = (P + c - 1) / c, nslots = a.period_keys / c;
-  const int np = (P + a.period_keys - 1) / a.period_keys;
+  const int L = pick(a.seq.seqlen, bl), P = L - a.window, c = a.chunk;
+  const int C = (P + c - 1) / c, S = kSingleHalf / c;
+  const int np = (P + kSinglePeriod - 1) / kSinglePeriod;   // periods that hold prefix keys
   const int p0 = blockIdx.x * kPeriodsPerGroup;
   if (p0 >= np) return;
   const int p1 = p0 + kPeriodsPerGroup < np ? p0 + kPeriodsPerGroup : np;
   const int nrows = (a.n_q_heads / a.n_kv_heads) * a.window;
-  const int passes = a.rows_pad / 64;
-  __shared__ float s_red[kPeriodsPerGroup][4][16];
+  __shared__ float s_ref[256];
 
-  float ref[kMaxRowPasses];
-#pragma unroll
-  for (int i = 0; i < kMaxRowPasses; ++i) {
-    const int row = (tid >> 2) + 64 * i;
-    ref[i] = (i < passes && row < nrows) ? a.refs[problem * a.rows_pad + row] : 3.0e38f;  // weight 0 for padding rows
-  }
-  // first slot of the quarter this thread reads: quarters are (half 0: 0..3, 8..11), (half 1: 4..7, 12..15)
-  const int q = tid & 3, slot0 = (q & 1) * 8 + (q >> 1) * 4;
-  for (int period = p0; period < p1; ++period) {
-    const int64_t pr = ((int64_t)problem * a.n_periods + period) * a.rows_pad;
-    const char *src = (const char *)a.e_buf + pr * kEBytesPerRowMisc;
-    const float *mp = a.m_period + pr;
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < kMaxRowPasses; ++i) {
-      if (i < passes) {
-        const float wgt = exp2f(mp[(tid >> 2) + 64 * i] - ref[i]);
-        const u32x3 d = *(const u32x3 *)(src + (tid + 256 * i) * 12);
-        const f32x4 x = {__uint_as_float(d.x << 8), __uint_as_float(__builtin_amdgcn_alignbit(d.y, d.x, 24) << 8),
-                         __uint_as_float(__builtin_amdgcn_alignbit(d.z, d.y, 16) << 8), __uint_as_float(d.z & 0xFFFFFF00u)};
-        v += x * wgt;
+  // ---- references
+  {
+    const int nsplit = ((L + kSinglePeriod - 1) / kSinglePeriod + a.tiles_per_wg - 1) / a.tiles_per_wg;
+    float m = -1.0e30f, l = 0.f;
+    if (tid < nrows) {
+      const float2 *ps = a.part_stats + (problem * a.max_split * a.rows_pad + tid) * 2;
+      for (int s = 0; s < nsplit; ++s) {
+        const float4 x = *(const float4 *)(ps + (int64_t)s * a.rows_pad * 2);   // both lane halves of the row
+        float mm = fmaxf(m, x.x);
+        l = l * exp2f(m - mm) + x.y * exp2f(x.x - mm);
+        m = mm;
+        mm = fmaxf(m, x.z);
+        l = l * exp2f(m - mm) + x.w * exp2f(x.z - mm);
+        m = mm;
       }
     }
-#pragma unroll
-    for (int o = 4; o < 64; o <<= 1) {
-      v.x += __shfl_xor(v.x, o); v.y += __shfl_xor(v.y, o); v.z += __shfl_xor(v.z, o); v.w += __shfl_xor(v.w, o);
-    }
-    if (lane < 4) *(f32x4 *)&s_red[period - p0][wave][slot0] = v;
+    s_ref[tid] = tid < nrows ? m + log2f(l) : 3.0e38f;
   }
   __syncthreads();
-  if (tid < kPeriodsPerGroup * 16) {
-    const int pi = tid >> 4, slot = tid & 15, period = p0 + pi;
-    const int chunk = period * nslots + slot;
-    if (period < p1 && slot < nslots && chunk < C)
-      a.chunk_scores[problem * a.score_cap + chunk] =
-          (s_red[pi][0][slot] + s_red[pi][1][slot]) + (s_red[pi][2][slot] + s_red[pi][3][slot]);
+
+  // ---- chunk scores
+  const int parts = S / 4, combos = 2 * parts;
+  const char *e_problem = (const char *)a.e_buf + problem * a.n_periods * a.rows_pad * (int64_t)(6 * S);
+  const float *m_problem = a.m_period + problem * a.n_periods * a.rows_pad * 2;
+  for (int task = wave; task < (p1 - p0) * combos; task += 4) {
+    const int period = p0 + task / combos, combo = task % combos;
+    const int hh = combo / parts, part = combo % parts;
+    const char *src = e_problem + ((int64_t)(period * 2 + hh) * parts + part) * a.rows_pad * 12;
+    const float *mp = m_problem + (int64_t)(period * 2 + hh) * a.rows_pad;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    for (int row = lane; row < nrows; row += 64) {
+      const float wgt = exp2f(mp[row] - s_ref[row]);
+      const u32x3 d = *(const u32x3 *)(src + row * 12);
+      const f32x4 x = {__uint_as_float(d.x << 8), __uint_as_float(__builtin_amdgcn_alignbit(d.y, d.x, 24) << 8),
+                       __uint_as_float(__builtin_amdgcn_alignbit(d.z, d.y, 16) << 8), __uint_as_float(d.z & 0xFFFFFF00u)};
+      v += x * wgt;
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      v.x += __shfl_xor(v.x, o); v.y += __shfl_xor(v.y, o); v.z += __shfl_xor(v.z, o); v.w += __shfl_xor(v.w, o);
+    }
+    if (lane < 4) {
+      const int chunk = period * 2 * S + 2 * (4 * part + lane) + hh;
+      const float val = lane == 0 ? v.x : (lane == 1 ? v.y : (lane == 2 ? v.z : v.w));
+      if (chunk < C) a.chunk_scores[problem * a.score_cap + chunk] = val;
+    }
   }
 }
 
-int launch_fused_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s) {
+int launch_single_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slice, hipStream_t s) {
   int max_periods = 0;
   for (int b = 0; b < batch_slice; ++b) {
     const int P = a.seq.seqlen[b] - a.window;
-    const int np = (P + a.period_keys - 1) / a.period_keys;
+    const int np = (P + kSinglePeriod - 1) / kSinglePeriod;
     max_periods = np > max_periods ? np : max_periods;
   }
   if (max_periods == 0 || n_leaders_slice <= 0) return CHUNKKV_OK;
-  if (a.rows_pad % 64 != 0 || a.rows_pad > kMaxRows) return CHUNKKV_ERR_UNSUPPORTED;
+  if (a.rows_pad > 256 || kSingleHalf % a.chunk != 0 || (kSingleHalf / a.chunk) % 4 != 0) return CHUNKKV_ERR_UNSUPPORTED;
   dim3 grid((max_periods + kPeriodsPerGroup - 1) / kPeriodsPerGroup, batch_slice * a.n_kv_heads, n_leaders_slice);
-  hipLaunchKernelGGL(fused_scores_kernel, grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL(single_scores_kernel, grid, dim3(256), 0, s, a);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 

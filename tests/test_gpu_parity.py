@@ -512,19 +512,22 @@ def test_stack_call_replays_from_a_hip_graph(lib):
 
 
 # ------------------------------------------------------------------ extreme logit spread
+@pytest.mark.parametrize("window", [32, 64])
 @pytest.mark.parametrize("kscale", [10.0, 40.0])
-def test_scores_under_extreme_logit_spread(lib, scoring_path, kscale):
-    """Keys scaled by 10 (40): the logits of a row spread over ~80 (~300) nats and the mass sits in a few keys.  The two-pass kernels (fp32 exponentials) keep the relative bar on every chunk.  The single-pass
-    kernel rounds each exponential to fp16 relative to the row's reference, so what lies more than 2^-36 below
-    that reference is flushed: every chunk is within 1e-3 relative plus 1e-7 absolute (of a head mass of
-    g*w = 128), and the chunks that matter for any realistic budget - here the upper half by score - keep the
-    relative bar alone."""
-    wl = small("llama8b_8k", n_q_heads=8, n_kv_heads=2, seqlens=(3000,), n_spans=(6,))
+def test_scores_under_extreme_logit_spread(lib, scoring_path, kscale, window):
+    """Keys scaled by 10 (40): the logits of a row spread over ~80 (~300) nats, the mass sits in a few keys and
+    the chunk scores span twenty orders of magnitude.  Both scoring paths keep exponentials and sums in fp32, so
+    the plain relative bar holds on every chunk, and a selection that keeps 90 % of the tokens (which reaches
+    deep into the chunks that hold almost no mass) stays inside the tie band.  window 32 / 64: 128 / 256 window
+    rows per kv-head (one and two row blocks per wavefront in the single-pass kernel)."""
+    wl = small("llama8b_8k", n_q_heads=8, n_kv_heads=2, window=window, seqlens=(3000,), n_spans=(6,), keep_pct=90)
     li = W.make_layer(wl, 0, DEV)
     li.k.mul_(kscale)                    # re-rounded to bf16 once; both sides read the same stored bits
     prob = H.make_problem(lib, wl, li)
     cs = torch.zeros((1, wl.n_kv_heads, prob.score_cap), dtype=torch.float32, device=DEV)
     lib.chunkkv_score(prob, li.q, li.k, cs, None, workspace(lib, prob))
+    sel = alloc_sel(prob)
+    lib.chunkkv_chunk_topk(prob, cs, *sel)
     torch.cuda.synchronize()
     q, k, _ = H.seq_arrays(wl, li, 0)
     o_cs, _ = orc.score(q, k, wl.window, wl.chunk)
@@ -532,13 +535,13 @@ def test_scores_under_extreme_logit_spread(lib, scoring_path, kscale):
     got = cs[0, :, :C].cpu().numpy().astype(np.float64)
     rel = np.abs(got - o_cs) / o_cs
     print(f"{scoring_path}: chunk scores span {o_cs.min():.2e} .. {o_cs.max():.2e}; max relative error {rel.max():.2e}")
-    if scoring_path == "two_pass":
-        assert rel.max() <= H.REL_TOL
-    else:
-        assert np.all(np.abs(got - o_cs) <= H.REL_TOL * o_cs + 1e-7)
-        for h in range(wl.n_kv_heads):
-            top = np.argsort(-o_cs[h])[:C // 2]
-            assert rel[h][top].max() <= H.REL_TOL
+    assert rel.max() <= H.REL_TOL
+    P, n_keep = wl.seqlens[0] - wl.window, int(prob.n_keep[0])
+    g_sel = H.read_selection(prob, *sel)
+    differ = 0
+    for h in range(wl.n_kv_heads):
+        differ += H.check_selection(g_sel[0][h], orc.chunk_topk(o_cs[h], P, wl.chunk, n_keep), o_cs[h], P, wl.chunk, n_keep)
+    print(f"keep 90 %: {differ} chunks differ, all inside the tie band")
 
 
 # ------------------------------------------------------------------ seeded sweep of random shapes
