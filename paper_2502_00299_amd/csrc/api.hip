@@ -223,7 +223,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
       if (np > pl->n_periods) pl->n_periods = np;
     }
     // the kernels address E of one problem with 32-bit byte offsets
-    if ((int64_t)pl->n_periods * pl->rows_pad_s * 96 >= (int64_t)1 << 32) pl->single_ok = 0;
+    if ((int64_t)pl->n_periods * pl->rows_pad_s * 80 >= (int64_t)1 << 32) pl->single_ok = 0;
     // key-range length in periods: at most kTargetWorkgroupsSingle workgroups, and ranges of at least 16 periods
     // (so that a workgroup's start-up stays small) unless that would leave fewer workgroups than the chip
     // holds at once (512)
@@ -241,7 +241,7 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   const size_t problems = (size_t)pl->n_leaders * p->batch * p->n_kv_heads;
   size_t part_bytes = problems * pl->max_split0 * pl->rows_pad * sizeof(float2);
   if (pl->single_ok) {
-    const size_t pb = problems * pl->max_split_s * pl->rows_pad_s * 2 * sizeof(float2);
+    const size_t pb = problems * pl->max_split_s * pl->rows_pad_s * sizeof(float2);
     part_bytes = pb > part_bytes ? pb : part_bytes;
   }
   size_t off = 0;
@@ -253,8 +253,9 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   if (!pl->fuse_chunks) off += align256(problems * (size_t)p->score_cap * p->chunk * sizeof(float));
   pl->off_ebuf = pl->off_mper = off;
   if (pl->single_ok) {
-    const size_t cells = problems * (size_t)pl->n_periods * pl->rows_pad_s * 2;   // (period, row, lane half)
-    pl->off_ebuf = off; off += align256(cells * (size_t)(3 * (80 / p->chunk)));
+    const size_t cells = problems * (size_t)pl->n_periods * pl->rows_pad_s;   // (period, row)
+    const int sums = 80 / p->chunk;   // chunk sums per lane half and period: 20-bit floats in groups of eight, else 24-bit
+    pl->off_ebuf = off; off += align256(cells * (size_t)(sums == 4 ? 24 : 5 * sums));
     pl->off_mper = off; off += align256(cells * sizeof(float));
   }
   pl->total = off < 256 ? 256 : off;

@@ -48,8 +48,7 @@ struct ScoreArgs {
   // single-pass path (score_single.h): key ranges are whole periods of 160 keys (tiles_per_wg counts periods)
   int32_t n_periods;       // pitch of e_buf / m_period: max over sequences of ceil(L / 160)
   void *e_buf;             // [problem][n_periods][rows_pad][2 lane halves][80 / c] x 3 bytes: per-(chunk, row) sums of e
-  float *m_period;         // [problem][n_periods][rows_pad][2]  reference those sums are relative to
-                           // part_stats is [problem][max_split][rows_pad][2] on this path
+  float *m_period;         // [problem][n_periods][rows_pad]  reference those sums are relative to
 };
 
 // Caller-supplied row log-sum-exps -> row references of the importance pass.

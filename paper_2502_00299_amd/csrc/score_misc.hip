@@ -140,16 +140,17 @@ int launch_chunk_sums(const ScoreArgs &a, int n_leaders_slice, int batch_slice, 
 }
 
 // Single-pass path, second kernel: the row references and the chunk scores.
-//   ref_r = m_r + log2(sum_r), merged from the (reference, sum) pairs every key range and lane half of row r left
-//           (pairs merge associatively; always in the same order: range by range, lane half 0 first);
+//   ref_r = m_r + log2(sum_r), merged from the (reference, sum) pairs the key ranges left for row r
+//           (pairs merge associatively; always in the same order: range by range);
 //   score[chunk] = sum over rows of E[chunk][row] * exp2(m[chunk][row] - ref[row]).
 // A workgroup of 256 threads merges the statistics of its problem (one row per thread) and then takes
 // kPeriodsPerGroup consecutive periods.  Per period the scoring kernel left, for each lane half h and each
-// group ("part") of four consecutive chunks of that half, rows_pad pieces of 12 bytes (four sums, each the upper
-// three bytes of an fp32), and per lane half rows_pad references.  A wavefront takes one (period, half, part)
-// at a time: its lanes walk the rows (a load instruction covers 768 contiguous bytes), weigh, and the four
-// sums are reduced over the lanes in a fixed order.  The chunk of (half h, part p, j) is 2 (4 p + j) + h of the
-// period's 2 S chunks.  Rows past the real ones are skipped: nothing was written for them.
+// group of eight consecutive chunks of that half, rows_pad pieces of 16 + 4 bytes (eight sums as 20-bit floats:
+// 8 exponent and 12 mantissa bits; chunk size 20 has four chunks per half: pieces of 12 bytes, four 24-bit
+// floats), and rows_pad references (one per row).  A wavefront takes one (period, half, group) at a time: its
+// lanes walk the rows (consecutive lanes read consecutive pieces), weigh, and the sums are reduced over the
+// lanes in a fixed order.  The chunk of (half h, position s) is 2 s + h of the period's 2 S chunks.  Rows past
+// the real ones are skipped: nothing was written for them.
 // grid: x = period group, y = (sequence, kv-head), z = leader.
 constexpr int kPeriodsPerGroup = 32;
 constexpr int kSinglePeriod = 160, kSingleHalf = 80;   // as in the single-pass scoring kernel
@@ -174,14 +175,11 @@ __global__ __launch_bounds__(256) void single_scores_kernel(ScoreArgs a) {
     const int nsplit = ((L + kSinglePeriod - 1) / kSinglePeriod + a.tiles_per_wg - 1) / a.tiles_per_wg;
     float m = -1.0e30f, l = 0.f;
     if (tid < nrows) {
-      const float2 *ps = a.part_stats + (problem * a.max_split * a.rows_pad + tid) * 2;
+      const float2 *ps = a.part_stats + problem * a.max_split * a.rows_pad + tid;
       for (int s = 0; s < nsplit; ++s) {
-        const float4 x = *(const float4 *)(ps + (int64_t)s * a.rows_pad * 2);   // both lane halves of the row
-        float mm = fmaxf(m, x.x);
+        const float2 x = ps[(int64_t)s * a.rows_pad];
+        const float mm = fmaxf(m, x.x);
         l = l * exp2f(m - mm) + x.y * exp2f(x.x - mm);
-        m = mm;
-        mm = fmaxf(m, x.z);
-        l = l * exp2f(m - mm) + x.w * exp2f(x.z - mm);
         m = mm;
       }
     }
@@ -190,30 +188,72 @@ __global__ __launch_bounds__(256) void single_scores_kernel(ScoreArgs a) {
   __syncthreads();
 
   // ---- chunk scores
-  const int parts = S / 4, combos = 2 * parts;
-  const char *e_problem = (const char *)a.e_buf + problem * a.n_periods * a.rows_pad * (int64_t)(6 * S);
-  const float *m_problem = a.m_period + problem * a.n_periods * a.rows_pad * 2;
-  for (int task = wave; task < (p1 - p0) * combos; task += 4) {
-    const int period = p0 + task / combos, combo = task % combos;
-    const int hh = combo / parts, part = combo % parts;
-    const char *src = e_problem + ((int64_t)(period * 2 + hh) * parts + part) * a.rows_pad * 12;
-    const float *mp = m_problem + (int64_t)(period * 2 + hh) * a.rows_pad;
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    for (int row = lane; row < nrows; row += 64) {
-      const float wgt = exp2f(mp[row] - s_ref[row]);
-      const u32x3 d = *(const u32x3 *)(src + row * 12);
-      const f32x4 x = {__uint_as_float(d.x << 8), __uint_as_float(__builtin_amdgcn_alignbit(d.y, d.x, 24) << 8),
-                       __uint_as_float(__builtin_amdgcn_alignbit(d.z, d.y, 16) << 8), __uint_as_float(d.z & 0xFFFFFF00u)};
-      v += x * wgt;
-    }
+  const int64_t prow = (int64_t)a.rows_pad;
+  const float *m_problem = a.m_period + problem * a.n_periods * prow;
+  if (S == 4) {
+    // [lane half][rows_pad] x 12 bytes: four sums as the upper three bytes of their fp32
+    const char *e_problem = (const char *)a.e_buf + problem * a.n_periods * prow * 24;
+    for (int task = wave; task < (p1 - p0) * 2; task += 4) {
+      const int period = p0 + task / 2, hh = task % 2;
+      const char *src = e_problem + ((int64_t)period * 2 + hh) * prow * 12;
+      const float *mp = m_problem + (int64_t)period * prow;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      for (int row = lane; row < nrows; row += 64) {
+        const float wgt = exp2f(mp[row] - s_ref[row]);
+        const u32x3 d = *(const u32x3 *)(src + row * 12);
+        const f32x4 x = {__uint_as_float(d.x << 8), __uint_as_float(__builtin_amdgcn_alignbit(d.y, d.x, 24) << 8),
+                         __uint_as_float(__builtin_amdgcn_alignbit(d.z, d.y, 16) << 8), __uint_as_float(d.z & 0xFFFFFF00u)};
+        v += x * wgt;
+      }
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      v.x += __shfl_xor(v.x, o); v.y += __shfl_xor(v.y, o); v.z += __shfl_xor(v.z, o); v.w += __shfl_xor(v.w, o);
+      for (int o = 1; o < 64; o <<= 1) {
+        v.x += __shfl_xor(v.x, o); v.y += __shfl_xor(v.y, o); v.z += __shfl_xor(v.z, o); v.w += __shfl_xor(v.w, o);
+      }
+      if (lane < 4) {
+        const int chunk = period * 2 * S + 2 * lane + hh;
+        const float val = lane == 0 ? v.x : (lane == 1 ? v.y : (lane == 2 ? v.z : v.w));
+        if (chunk < C) a.chunk_scores[problem * a.score_cap + chunk] = val;
+      }
     }
-    if (lane < 4) {
-      const int chunk = period * 2 * S + 2 * (4 * part + lane) + hh;
-      const float val = lane == 0 ? v.x : (lane == 1 ? v.y : (lane == 2 ? v.z : v.w));
-      if (chunk < C) a.chunk_scores[problem * a.score_cap + chunk] = val;
+  } else {
+    // groups of eight sums as 20-bit floats: [lane half][group][rows_pad] x 16 bytes, then x 4 bytes
+    const int G8 = S / 8, combos = 2 * G8;
+    const char *e_problem = (const char *)a.e_buf + problem * a.n_periods * prow * (combos * 20);
+    for (int task = wave; task < (p1 - p0) * combos; task += 4) {
+      const int period = p0 + task / combos, combo = task % combos;   // combo = half * G8 + group
+      const int hh = combo / G8, g8 = combo % G8;
+      const char *pbase = e_problem + (int64_t)period * prow * (combos * 20);
+      const char *src_lo = pbase + (int64_t)combo * prow * 16, *src_hi = pbase + (int64_t)combos * prow * 16 + (int64_t)combo * prow * 4;
+      const float *mp = m_problem + (int64_t)period * prow;
+      float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int row = lane; row < nrows; row += 64) {
+        const float wgt = exp2f(mp[row] - s_ref[row]);
+        const uint4 w = *(const uint4 *)(src_lo + row * 16);
+        const uint32_t w4 = *(const uint32_t *)(src_hi + row * 4);
+        uint32_t q[8];
+        q[0] = w.x & 0xFFFFFu;
+        q[1] = (w.x >> 20) | ((w.y & 0xFFu) << 12);
+        q[2] = (w.y >> 8) & 0xFFFFFu;
+        q[3] = (w.y >> 28) | ((w.z & 0xFFFFu) << 4);
+        q[4] = (w.z >> 16) | ((w.w & 0xFu) << 16);
+        q[5] = (w.w >> 4) & 0xFFFFFu;
+        q[6] = (w.w >> 24) | ((w4 & 0xFFFu) << 8);
+        q[7] = w4 >> 12;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] += __uint_as_float(q[i] << 11) * wgt;
+      }
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] += __shfl_xor(v[i], o);
+      }
+      if (lane < 8) {
+        float val = v[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) val = lane == i ? v[i] : val;
+        const int chunk = period * 2 * S + 2 * (8 * g8 + lane) + hh;
+        if (chunk < C) a.chunk_scores[problem * a.score_cap + chunk] = val;
+      }
     }
   }
 }

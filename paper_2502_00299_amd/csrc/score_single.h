@@ -16,8 +16,7 @@
 // of a period alternate between the halves (half h owns chunks h, h + 2, ...), and register v of step t of a
 // period holds position u = 16 t + v of the lane half's own sequence of 80 keys.  Position u belongs to own
 // chunk u / c: a compile-time function of (t, v), so every exponential is added to its chunk's register with
-// one plain add, no matrix product and no cross-lane traffic, and the two halves of a row never have to agree
-// on a reference.
+// one plain add, no matrix product and no cross-lane traffic.
 //
 // The reference is lazy.  fp32 has room for e up to 2^100 before the sums are in danger, so the reference moves
 // only when a step's sum reaches that bound (the first step of a range always does, its reference starts at
@@ -67,6 +66,19 @@ __device__ __forceinline__ u32x3 pack24(float x, float y, float z, float w) {
   const uint32_t c = __float_as_uint(z) + 0x80u, d = __float_as_uint(w) + 0x80u;
   return u32x3{__builtin_amdgcn_perm(b, a, 0x05030201u), __builtin_amdgcn_perm(c, b, 0x06050302u),
                __builtin_amdgcn_perm(d, c, 0x07060503u)};
+}
+
+// eight non-negative finite fp32 values -> their upper 20 bits below the sign (8 exponent, 12 mantissa bits,
+// rounded: relative 2^-13), packed into five dwords
+__device__ __forceinline__ void pack20(const float (&v)[8], u32x4 &lo, uint32_t &hi) {
+  uint32_t q[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) q[i] = (__float_as_uint(v[i]) + 0x400u) >> 11;
+  lo.x = q[0] | (q[1] << 20);
+  lo.y = (q[1] >> 12) | (q[2] << 8) | (q[3] << 28);
+  lo.z = (q[3] >> 4) | (q[4] << 16);
+  lo.w = (q[4] >> 16) | (q[5] << 4) | (q[6] << 24);
+  hi = (q[6] >> 8) | (q[7] << 12);
 }
 
 // period-relative key of position u of lane half 0's own sequence (lane half 1: + C)
@@ -189,13 +201,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_single_kernel(ScoreArgs a) 
   // block are resident; fragment ks is re-read for the next block right behind its last product.
   f32x16 acc[2];
   u32x4 kf[NKS];
-  // E and the references of this problem (byte offsets inside stay below 2^32).  Layout per period:
-  // E [lane half][S / 4 parts][rows_pad] x 12 bytes (four sums of 3 bytes), m [lane half][rows_pad] floats.
-  char *e_problem = (char *)a.e_buf + (int64_t)problem * a.n_periods * a.rows_pad * (2 * 3 * S);
-  char *m_problem = (char *)a.m_period + (int64_t)problem * a.n_periods * a.rows_pad * 8;
+  // E and the references of this problem (byte offsets inside stay below 2^32).  Layout per period, with a
+  // group = eight chunk sums of one lane half as 20-bit floats: [lane half][group][rows_pad] x 16 bytes, then
+  // [lane half][group][rows_pad] x 4 bytes (c = 20 has four sums per lane half: [lane half][rows_pad] x 12 bytes,
+  // 24-bit floats); m [rows_pad] floats.  Consecutive lanes write consecutive pieces.
+  constexpr int G8 = S / 8;                                  // groups of eight sums per lane half
+  constexpr int kPeriodRowBytes = S == 4 ? 24 : 2 * G8 * 20;  // E bytes per period and row
+  char *e_problem = (char *)a.e_buf + (int64_t)problem * a.n_periods * a.rows_pad * kPeriodRowBytes;
+  char *m_problem = (char *)a.m_period + (int64_t)problem * a.n_periods * a.rows_pad * 4;
   const uint32_t lane_row = (uint32_t)(wave * NQ * 32 + n);
-  const uint32_t lane_e = ((uint32_t)half * (S / 4) * (uint32_t)a.rows_pad + lane_row) * 12u;
-  const uint32_t lane_m = ((uint32_t)half * (uint32_t)a.rows_pad + lane_row) * 4u;
+  const uint32_t lane_m = lane_row * 4u;
   const int key_half = C * half;  // period-relative key of the lane half's position 0
 
   // logits of one micro-step; REFILL: the fragments are re-read from slot TR behind their product
@@ -335,7 +350,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_single_kernel(ScoreArgs a) 
           if constexpr (MASKED) xv = (pkey0 + key_half + sp_key<C>(16 * T + v)) <= lim[QI] ? xv : -3.0e38f;
           bm = fmaxf(bm, xv);
         }
-        const float m_new = tot >= kSpBig ? bm * c1 : m_run[QI];
+        // the two lane halves of a row move together, so a row has one reference per period
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        const bool mine = __shfl_xor(tot, 32) >= kSpBig || tot >= kSpBig;
+        const float m_new = mine ? bm * c1 : m_run[QI];
         const float f = fast_exp2(m_run[QI] - m_new);
 #pragma unroll
         for (int s = 0; s < S; ++s) slot[QI][s] *= f;
@@ -354,19 +372,31 @@ __global__ __launch_bounds__(kThreads, 2) void score_single_kernel(ScoreArgs a) 
       }
       if constexpr (MASKED) l_run[QI] += lw;
       if constexpr (T == kSpSteps - 1) {
-        // end of the period: the sums and the reference they are relative to leave the lane, each sum as the
-        // upper three bytes of its fp32 (rounded: relative 2^-17); consecutive lanes write consecutive pieces
+        // end of the period: the sums and the reference they are relative to leave the lane
         float sum = 0.f;
 #pragma unroll
         for (int s = 0; s < S; ++s) sum += slot[QI][s];
         l_run[QI] += sum;
         const uint32_t pbase = (uint32_t)(u0 + prel) * (uint32_t)a.rows_pad;
-        char *dst = e_problem + (pbase * (uint32_t)(6 * S) + lane_e + (uint32_t)(QI * 32 * 12));
+        const uint32_t rp = (uint32_t)a.rows_pad, row = lane_row + (uint32_t)(QI * 32);
+        char *pdst = e_problem + pbase * (uint32_t)kPeriodRowBytes;
+        if constexpr (S == 4) {
+          *(u32x3 *)(pdst + ((uint32_t)half * rp + row) * 12u) = pack24(slot[QI][0], slot[QI][1], slot[QI][2], slot[QI][3]);
+        } else {
 #pragma unroll
-        for (int s4 = 0; s4 < S / 4; ++s4)
-          *(u32x3 *)(dst + (uint32_t)s4 * (uint32_t)a.rows_pad * 12u) =
-              pack24(slot[QI][4 * s4], slot[QI][4 * s4 + 1], slot[QI][4 * s4 + 2], slot[QI][4 * s4 + 3]);
-        *(float *)(m_problem + (pbase * 8u + lane_m + (uint32_t)(QI * 32 * 4))) = m_run[QI];
+          for (int g8 = 0; g8 < G8; ++g8) {
+            float v8[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v8[i] = slot[QI][8 * g8 + i];
+            u32x4 lo;
+            uint32_t hi;
+            pack20(v8, lo, hi);
+            const uint32_t cell = ((uint32_t)(half * G8 + g8)) * rp + row;
+            *(u32x4 *)(pdst + cell * 16u) = lo;
+            *(uint32_t *)(pdst + (uint32_t)(2 * G8) * rp * 16u + cell * 4u) = hi;
+          }
+        }
+        if (half == 0) *(float *)(m_problem + (pbase * 4u + lane_m + (uint32_t)(QI * 32 * 4))) = m_run[QI];
       }
     }
   };
@@ -418,12 +448,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_single_kernel(ScoreArgs a) 
     }
   }
 
-  // per-range (reference, sum) of every (row, lane half) for the merge
+  // per-range (reference, sum) of every row for the merge (the lane halves share the reference)
   if (active) {
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
       const int row = (wave * NQ + qi) * 32 + n;
-      a.part_stats[((problem * a.max_split + split) * a.rows_pad + row) * 2 + half] = make_float2(m_run[qi], l_run[qi]);
+      const float l = l_run[qi] + __shfl_xor(l_run[qi], 32);
+      if (half == 0) a.part_stats[(problem * a.max_split + split) * a.rows_pad + row] = make_float2(m_run[qi], l);
     }
   }
 }
