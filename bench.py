@@ -39,6 +39,19 @@ def algorithmic_bytes(wl, n_keep, n_layers, reuse):
             "stack": leaders * k_read + n_layers * gather}
 
 
+def csrc_hash():
+    """sha256 over the library's sources (file names and contents, sorted): what profiles/hbm_traffic.json is tied to."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2502_00299_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    h.update(open(os.path.join(ROOT, "include", "chunkkv.h"), "rb").read())
+    return h.hexdigest()
+
+
 def ckv_single_pass_used(kern):
     """The single-pass path launches no chunk-sum kernel and its row reduction is far shorter than its
     scoring kernel; the two-pass kernels take about the same time each."""
@@ -54,11 +67,12 @@ def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers, gpu_sel=None):
     layers are then compared with the oracle's (chunks that differ, and whether all of them lie inside the
     1e-3 relative tie band around the oracle's threshold score)."""
     from oracle import chunkkv_oracle as orc
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
     try:
         from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        threads = os.cpu_count() or 1
+        blas_threads = None
     host = []
     for l in range(n_sample_layers):
         li = layers[l]
@@ -89,8 +103,10 @@ def cpu_baseline(wl, layers, n_keep, reuse, n_sample_layers, gpu_sel=None):
             cpu = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), None)
     except OSError:
         pass
-    out = {"value": sum(wl.seqlens) / est_stack, "unit": "prefix tokens/s", "cores": int(threads),
-           "kind": "oracle", "cpu": cpu,
+    out = {"value": sum(wl.seqlens) / est_stack, "unit": "prefix tokens/s", "cores": int(cores),
+           "kind": "oracle", "cpu": cpu, "blas_threads": blas_threads,
+           "threading": "cores = CPUs this process may run on (sched_getaffinity); the oracle is numpy: only its matrix "
+                        "products run on the BLAS thread pool, exp / where / sum are single-threaded",
            "sample": f"layers 0..{n_sample_layers - 1} of {wl.n_layers} (all sequences and kv-heads) in "
                      f"{dt:.1f} s, scaled by {wl.n_layers}/{n_sample_layers}"}
     if gpu_sel is not None:
@@ -146,11 +162,14 @@ def main():
     ap.add_argument("--no-streaming", action="store_true", help="skip the per-layer streaming-call leg")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
-    ap.add_argument("--overlap", type=int, default=0,
-                    help="k > 0: score the leader layers in k sets and gather each set on a helper stream")
+    ap.add_argument("--csrc-hash", action="store_true", help="print the hash profiles/hbm_traffic.json must name, and exit")
+    ap.add_argument("--no-other", action="store_true", help="skip the other-workloads leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.csrc_hash:
+        print(csrc_hash())
+        return
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
         sys.exit(2)
@@ -160,7 +179,6 @@ def main():
 
     import paper_2502_00299_amd as ckv
     ckv.load_library()
-    ckv.chunkkv_set_overlap(args.overlap)
     dev = "cuda:0"
     wl = W.get_workload(args.workload)
     if args.keep_pct is not None:
@@ -257,10 +275,17 @@ def main():
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                 "algorithmic_bytes_per_launch": bytes_per_launch}
+    # HBM bytes per launch from rocprofv3 counters (profiles/hbm_traffic.json): valid only for the kernel sources
+    # they were taken from, so the file names their hash and the figure is dropped when the sources have changed
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):
         try:
-            roofline["traffic"] = json.load(open(traffic_file)).get(wl.name, {}).get(dom)
+            tf = json.load(open(traffic_file))
+            if tf.get("csrc_sha256") == csrc_hash():
+                roofline["traffic"] = tf.get(wl.name, {}).get(dom)
+            else:
+                log("bench.py: profiles/hbm_traffic.json was taken from other kernel sources (csrc hash differs): "
+                    "roofline.traffic = null until the counters are collected again")
         except Exception:
             pass
     stack_gbps = ab["stack"] / (ms * 1e-3) / 1e9
@@ -394,7 +419,9 @@ def main():
     out = {
         "metric": "prefix tokens compressed/sec (32-layer stack) + achieved HBM GB/s vs peak",
         "value": value, "unit": "prefix tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "step_ms_hip_events": step_spread, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "ms_per_step": ms, "ms_per_step_source": "wall clock over the K timed steps between two device synchronisations, / K "
+                                                 "(value uses it); step_ms_hip_events: single steps between HIP events",
+        "step_ms_hip_events": step_spread, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {N} layers, B={wl.batch}, L={list(wl.seqlens)}, Hq={wl.n_q_heads}, "
                                f"Hkv={wl.n_kv_heads}, d={wl.head_dim}, w={wl.window}, c={wl.chunk}, "
@@ -422,6 +449,58 @@ def main():
         out["cpu_baseline"] = cpu_baseline(wl, layers, n_keep, R, n_cpu, gpu_sel=main_sel())
     else:
         out["cpu_baseline"] = None
+
+    # the other configurations of the benchmark spec, each one chunkkv_compress_stack call per step on its own inputs
+    # (not the headline; reported so that every configuration has a recorded figure)
+    other = None
+    if not args.no_other and args.workload == "llama8b_128k_stack":
+        other = {}
+
+        def quick(tag, wl2, layers2, R2):
+            try:
+                N2 = wl2.n_layers
+                nk2 = [W.keep_budget(L, wl2.window, wl2.keep_pct) for L in wl2.seqlens]
+                l0 = layers2[0]
+                p2 = ckv.Problem(wl2.n_q_heads, wl2.n_kv_heads, wl2.head_dim, wl2.window, wl2.chunk,
+                                 {"f32": ckv.F32, "bf16": ckv.BF16, "f16": ckv.F16}[wl2.dtype], list(wl2.seqlens), nk2,
+                                 list(l0.kv_base), l0.kv_stride_head, l0.kv_stride_tok)
+                ko = [torch.empty(p2.out_elements(), dtype=wl2.torch_dtype, device=dev) for _ in range(N2)]
+                vo = [torch.empty(p2.out_elements(), dtype=wl2.torch_dtype, device=dev) for _ in range(N2)]
+                G2 = (N2 + R2 - 1) // R2
+                sc2 = torch.zeros((G2, wl2.batch, wl2.n_kv_heads, p2.sel_cap), dtype=torch.int32, device=dev)
+                sl2, cn2 = torch.zeros_like(sc2), torch.zeros((G2, wl2.batch, wl2.n_kv_heads), dtype=torch.int32, device=dev)
+                ws2 = torch.empty(ckv.chunkkv_workspace_bytes(p2, N2, R2), dtype=torch.uint8, device=dev)
+                q2 = [layers2[l].q if l % R2 == 0 else None for l in range(N2)]
+                k2, v2 = [x.k for x in layers2], [x.v for x in layers2]
+
+                def run2():
+                    ckv.chunkkv_compress_stack(p2, R2, q2, k2, v2, ko, vo, sc2, sl2, cn2, ws2)
+                ms2, _ = timed(run2, args.steps, args.warmup)
+                ab2 = algorithmic_bytes(wl2, nk2, N2, R2)
+                other[tag] = {"ms_per_step": ms2, "value": sum(wl2.seqlens) / (ms2 * 1e-3), "unit": "prefix tokens/s",
+                              "stack_hbm_frac": ab2["stack"] / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                              "algorithmic_bytes": ab2["stack"]}
+            except Exception as e:
+                log(f"other workload {tag} failed: {e!r}")
+
+        quick("llama8b_128k_stack keep 20% R=2", wl.with_(keep_pct=20), layers, 2)
+        del layers, ks, vs, k_out, v_out
+        torch.cuda.empty_cache()
+        wl3 = W.get_workload("llama8b_32k_stack")
+        log(f"generating {wl3.name}")
+        layers3 = [W.make_layer(wl3, l, dev) for l in range(wl3.n_layers)]
+        quick("llama8b_32k_stack keep 10% R=1", wl3, layers3, 1)
+        quick("llama8b_32k_stack keep 10% R=2", wl3, layers3, 2)
+        del layers3
+        torch.cuda.empty_cache()
+        wl5 = W.get_workload("ragged_b8")
+        log(f"generating {wl5.name}")
+        layers5 = [W.make_layer(wl5, l, dev) for l in range(wl5.n_layers)]
+        quick("ragged_b8 c=10 keep 10% R=2", wl5, layers5, 2)
+        quick("ragged_b8 c=5 keep 30% R=3", wl5.with_(chunk=5, keep_pct=30), layers5, 3)
+        quick("ragged_b8 c=20 keep 20% R=1", wl5.with_(chunk=20, keep_pct=20), layers5, 1)
+        del layers5
+    out["other_workloads"] = other
     print(json.dumps(out), flush=True)
 
 

@@ -12,9 +12,11 @@
  *   g = Hq / Hkv                               d  head dim               n_keep  candidate tokens kept
  *   n_kept = n_keep + w  (L_max in the paper)  R  reuse depth (N_reuse in the paper)
  *
- * Every pointer named "device" is GPU memory owned by the caller; the library never allocates,
- * frees or synchronises.  All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
- * the default stream).  Host arrays inside chunkkv_problem and the per-layer pointer tables are
+ * Every pointer named "device" is GPU memory owned by the caller.  No call allocates or frees device
+ * memory and none synchronises the device; the one exception is the measurement aid at the end of this
+ * file (chunkkv_timing_begin creates HIP events, chunkkv_timing_end waits for them and destroys them).
+ * All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream); there is
+ * no process-wide setting: what a call does depends on its arguments alone.  Host arrays inside chunkkv_problem and the per-layer pointer tables are
  * read before the call returns.  Inputs are never written; outputs must not alias inputs.
  * Inputs containing NaN/Inf give undefined results (no fault).
  *
@@ -64,7 +66,20 @@ typedef struct {
   int64_t out_stride_head, out_stride_tok;
   int32_t sel_cap;              /* >= max_b ceil(n_keep_b / c) + 1 : row pitch of sel_chunk/sel_len */
   int32_t score_cap;            /* >= max_b ceil(P_b / c)          : row pitch of chunk_scores      */
+  uint32_t flags;               /* CHUNKKV_FLAG_* bits, 0 = defaults; unknown bits: CHUNKKV_ERR_UNSUPPORTED */
 } chunkkv_problem;
+
+/* chunkkv_problem.flags
+ * CHUNKKV_FLAG_WHOLE_CHUNKS  selection as Algorithm 3 prints it (Appendix A.5): k = min(floor(n_keep / c), C)
+ *     chunks are kept whole and nothing is cut, so a head keeps k*c tokens, or fewer when the ragged last
+ *     chunk is among them.  In chunkkv_compact / chunkkv_compress_* the window then follows the kept tokens
+ *     directly, rows past kept + w of an output head are left untouched, and the caller reads the kept count
+ *     of a head as the sum of its sel_len entries.  Default (bit clear): exactly n_keep tokens are kept, the
+ *     lowest-ranked selected chunk is cut to its leading tokens.
+ * CHUNKKV_FLAG_TWO_PASS  score with the general two-pass kernels even where the single-pass kernel applies
+ *     (same results to rounding; see chunkkv_score).                                                       */
+#define CHUNKKV_FLAG_WHOLE_CHUNKS 1u
+#define CHUNKKV_FLAG_TWO_PASS 2u
 
 /* Selection descriptor (the paper's kept-index set I_l, Algorithm 2), per (sequence, kv-head):
  *   sel_count            number of entries
@@ -163,14 +178,6 @@ int chunkkv_compress_layer(const chunkkv_problem *prob, int32_t layer, int32_t r
 int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t *sel_chunk, const int32_t *sel_len,
                     const int32_t *sel_count, float *jaccard, void *stream);
 
-/* Selection mode of all subsequent calls (process-wide).  0 (default): exactly n_keep tokens are kept, the
- * lowest-ranked selected chunk is cut to its leading tokens.  1: Algorithm 3 as printed in Appendix A.5 -
- * k = min(floor(n_keep / c), C) chunks are kept whole and nothing is cut, so a head keeps k*c tokens, or
- * fewer when the ragged last chunk is among them; in chunkkv_compact / chunkkv_compress_* the window then
- * follows the kept tokens directly, rows past kept + w of an output head are left untouched, and the caller
- * reads the kept count of a head as the sum of its sel_len entries.                                        */
-int chunkkv_set_whole_chunks(int32_t enable);
-
 /* Decoding over the (compressed) cache: the stage whose cache Eq. 1 sizes and whose latency Section 4.4
  * tabulates; Algorithm 1's output K', V' is its input.  One new query token per head attends to every
  * token of the cache of its kv-head (query head i reads kv-head i / g):
@@ -207,23 +214,10 @@ int chunkkv_decode_attention_static(const chunkkv_problem *prob, int32_t compact
                                     const void *q, const void *k, const void *v, float *out, float *lse,
                                     void *stream);
 
-/* Scoring has two implementations with the same results (to rounding): a single pass over K (bf16 and fp16 caches,
- * at least 65 window rows per kv-head, chunk sizes c with lcm(32, c) <= 256 keys and lcm(32, c) / c <= 16:
- * 10, 20, 40, 6, 12, 24, 14, 28, powers of two from 2 ...; not used when token_importance is requested) and a
- * general two-pass one.  The single pass rounds each exponential to fp16 relative to its row's running
- * reference: contributions more than 2^-36 below that reference are flushed, so chunks that hold essentially no
- * attention mass (scores below about 1e-7 of g*w) lose relative accuracy; the two-pass kernels do not.
- * chunkkv_set_single_pass(0) forces the two-pass kernels; the default is 1 (single pass where it applies). */
-int chunkkv_set_single_pass(int32_t enable);
-
-/* chunkkv_compress_stack normally scores all leader layers with one launch per kernel, selects, then
- * gathers all layers.  chunkkv_set_overlap(k) with k > 0 splits the leader layers into k sets and
- * enqueues the gather of a set on an internal helper stream (created on first use, default priority,
- * ordered after `stream`'s prior work and joined back into it with events before the call returns) so
- * that it can run beside the scoring of the next set.  The default is 0: one set, everything on
- * `stream` (on MI355X the split does not pay off: measured, scoring and gather that run side by side take as
- * long as one after the other).  The setting changes the launch plan: query chunkkv_workspace_bytes after it. */
-int chunkkv_set_overlap(int32_t sets);
+/* Scoring has two implementations with the same results (to rounding; both keep logits, exponentials and sums in
+ * fp32): a single pass over K (bf16 and fp16 caches of head_dim 128, 65 to 256 window rows per kv-head, chunk
+ * sizes 5, 10 and 20; not used when token_importance is requested) and a general two-pass one.
+ * CHUNKKV_FLAG_TWO_PASS in chunkkv_problem.flags selects the two-pass kernels for a call.                     */
 
 /* Measurement aid (the per-kernel durations the roofline figures need; Algorithm 2's T_compress and
  * T_select are the scoring+selection and the gather durations).  Between begin and end every kernel
@@ -233,7 +227,8 @@ int chunkkv_set_overlap(int32_t sets);
  *   0 score pass 0 (softmax statistics) or the single-pass kernel   1 statistics merge
  *   2 score pass 1 (importance, chunk sums) or the single-pass row reduction
  *   3 chunk sums for c larger than a key tile   4 chunk selection   5 compaction   6 decode attention
- * total_ms and launches are host arrays of CHUNKKV_TIMING_KINDS entries.  Not thread-safe.          */
+ * total_ms and launches are host arrays of CHUNKKV_TIMING_KINDS entries.  Process-wide and not thread-safe:
+ * one measurement at a time, no compression calls from other threads meanwhile.  It changes no result.   */
 #define CHUNKKV_TIMING_KINDS 7
 int chunkkv_timing_begin(int32_t max_records);
 int chunkkv_timing_end(double *total_ms, int64_t *launches);

@@ -7,6 +7,8 @@ from .binding import (  # noqa: F401
     BF16,
     F16,
     F32,
+    FLAG_TWO_PASS,
+    FLAG_WHOLE_CHUNKS,
     LIB_PATH,
     SYMBOLS,
     ChunkKVError,
@@ -22,9 +24,6 @@ from .binding import (  # noqa: F401
     chunkkv_jaccard,
     chunkkv_score,
     chunkkv_score_lse,
-    chunkkv_set_overlap,
-    chunkkv_set_single_pass,
-    chunkkv_set_whole_chunks,
     chunkkv_status_string,
     chunkkv_timing_begin,
     chunkkv_timing_end,

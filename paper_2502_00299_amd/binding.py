@@ -18,12 +18,11 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libchunkkv.so")
 
 F32, BF16, F16 = 0, 1, 2
+FLAG_WHOLE_CHUNKS, FLAG_TWO_PASS = 1, 2     # chunkkv_problem.flags
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
            "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_decode_workspace_bytes", "chunkkv_decode_attention",
            "chunkkv_decode_attention_static",
-           "chunkkv_set_overlap", "chunkkv_set_single_pass",
-           "chunkkv_set_whole_chunks",
            "chunkkv_timing_begin",
            "chunkkv_timing_end")
 TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact", "decode")
@@ -42,7 +41,7 @@ class _CProblem(C.Structure):
         ("seqlen", C.POINTER(C.c_int32)), ("n_keep", C.POINTER(C.c_int32)), ("kv_base", C.POINTER(C.c_int64)),
         ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
         ("out_base", C.POINTER(C.c_int64)), ("out_stride_head", C.c_int64), ("out_stride_tok", C.c_int64),
-        ("sel_cap", C.c_int32), ("score_cap", C.c_int32),
+        ("sel_cap", C.c_int32), ("score_cap", C.c_int32), ("flags", C.c_uint32),
     ]
 
 
@@ -66,6 +65,7 @@ class Problem:
     sel_cap: int = 0
     score_cap: int = 0
     softmax_scale: float = 0.0
+    flags: int = 0
 
     def __post_init__(self):
         c = self.chunk if self.chunk > 0 else 1
@@ -110,7 +110,7 @@ class Problem:
         cp = _CProblem(B, self.n_q_heads, self.n_kv_heads, self.head_dim, self.window, self.chunk, self.dtype,
                        self.softmax_scale, keep["seqlen"], keep["n_keep"], keep["kv_base"],
                        self.kv_stride_head, self.kv_stride_tok, keep["out_base"], self.out_stride_head,
-                       self.out_stride_tok, self.sel_cap, self.score_cap)
+                       self.out_stride_tok, self.sel_cap, self.score_cap, int(self.flags))
         cp._keep = keep
         return cp
 
@@ -283,27 +283,6 @@ def chunkkv_decode_attention_static(prob: Problem, compacted: bool, kv_len, q, k
     _check(load_library().chunkkv_decode_attention_static(
         C.byref(cp), 1 if compacted else 0, _ptr(kv_len), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
         _stream(stream)), "chunkkv_decode_attention_static")
-
-
-def chunkkv_set_single_pass(enable: bool) -> None:
-    lib = load_library()
-    lib.chunkkv_set_single_pass.restype = C.c_int
-    lib.chunkkv_set_single_pass.argtypes = [C.c_int32]
-    _check(lib.chunkkv_set_single_pass(1 if enable else 0), "chunkkv_set_single_pass")
-
-
-def chunkkv_set_whole_chunks(enable: bool) -> None:
-    lib = load_library()
-    lib.chunkkv_set_whole_chunks.restype = C.c_int
-    lib.chunkkv_set_whole_chunks.argtypes = [C.c_int32]
-    _check(lib.chunkkv_set_whole_chunks(1 if enable else 0), "chunkkv_set_whole_chunks")
-
-
-def chunkkv_set_overlap(enable: bool) -> None:
-    lib = load_library()
-    lib.chunkkv_set_overlap.restype = C.c_int
-    lib.chunkkv_set_overlap.argtypes = [C.c_int32]
-    _check(lib.chunkkv_set_overlap(int(enable)), "chunkkv_set_overlap")
 
 
 def chunkkv_timing_begin(max_records: int = 4096) -> None:

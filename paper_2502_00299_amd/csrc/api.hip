@@ -10,7 +10,6 @@ namespace ckv {
 namespace {
 
 constexpr int kTargetWorkgroups = 4096;  // ~4 resident rounds of 2 workgroups on each of 256 CUs
-constexpr int kTargetWorkgroupsSingle = 4096;  // single-pass kernel: finer ranges balance ragged batches, same speed on one long sequence
 constexpr int kSinglePeriodKeys = 160;   // granule of the single-pass kernel's key ranges
 // Key tiles (16 KB) one scoring launch set should hold.  Measured on MI355X: every extra dependent launch
 // costs ~30 us of idle GPU, more than splitting the stack into sets wins back, so one set it is.
@@ -23,7 +22,7 @@ struct Plan {
   int tpw0, tpw1, max_split0;
   int fuse_chunks;
   // single-pass path: usable for this problem?  geometry and workspace
-  int single_ok, rows_pad_s, n_periods, tpw_s, max_split_s;
+  int single_ok, rows_pad_s, n_periods, max_split_s;
   size_t off_part, off_refs, off_scores, off_seloff, off_imp, off_ebuf, off_mper, total;
 };
 
@@ -51,29 +50,6 @@ struct Timed {  // records an event pair around one launch when timing is on
     if (slot >= 0) (void)hipEventRecord(g_timing.ev[2 * slot + 1], s);
   }
 };
-
-// ---- helper stream for overlapping the gather with scoring inside chunkkv_compress_stack ----------
-bool g_whole_chunks = false;  // selection mode of all calls: exact budget (default) or whole chunks only
-int g_overlap_sets = 0;  // 0: one set, no helper stream; k > 0: k sets of leader layers, gather on the helper stream
-bool g_single_pass = true;  // use the single-pass scoring kernel where it applies
-struct Overlap {
-  hipStream_t side = nullptr;
-  static constexpr int kEvents = 128;
-  hipEvent_t ev[kEvents];
-  int cur = -1;
-  hipEvent_t next_event() { cur = (cur + 1) % kEvents; return ev[cur]; }
-  hipEvent_t last_event() const { return ev[cur]; }
-};
-Overlap *overlap_state() {  // created on first use; default priority; lives until the process ends
-  static Overlap *st = [] {
-    Overlap *o = new Overlap;
-    if (hipStreamCreateWithFlags(&o->side, hipStreamNonBlocking) != hipSuccess) { delete o; return (Overlap *)nullptr; }
-    for (int i = 0; i < Overlap::kEvents; ++i)
-      if (hipEventCreateWithFlags(&o->ev[i], hipEventDisableTiming) != hipSuccess) { delete o; return (Overlap *)nullptr; }
-    return o;
-  }();
-  return st;
-}
 
 // ---- device-resident scratch for chunkkv_decode_attention_static ---------------------------------
 // One array per GPU the library runs on, held until the process ends.  Its name is only a host-side
@@ -113,6 +89,7 @@ int check_problem(const chunkkv_problem *p, bool need_out) {
   if (p->n_q_heads % p->n_kv_heads != 0) return CHUNKKV_ERR_SHAPE;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return CHUNKKV_ERR_SHAPE;
   if (p->dtype != CHUNKKV_F32 && p->dtype != CHUNKKV_BF16 && p->dtype != CHUNKKV_F16) return CHUNKKV_ERR_UNSUPPORTED;
+  if (p->flags & ~(uint32_t)(CHUNKKV_FLAG_WHOLE_CHUNKS | CHUNKKV_FLAG_TWO_PASS)) return CHUNKKV_ERR_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return CHUNKKV_ERR_UNSUPPORTED;
   const int64_t rows = (int64_t)(p->n_q_heads / p->n_kv_heads) * p->window;
   ScoreGeom g;
@@ -175,7 +152,7 @@ int decode_plan(const chunkkv_problem *p, bool compacted, DecodePlan *pl) {
   return CHUNKKV_OK;
 }
 
-// Workspace layout and key-range split; a pure function of (problem, n_layers, reuse) and the overlap setting.
+// Workspace layout and key-range split; a pure function of (problem, n_layers, reuse).
 int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   if (n_layers < 1 || reuse < 1) return CHUNKKV_ERR_SHAPE;
   const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
@@ -194,7 +171,6 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   // few enough that compaction of one set overlaps scoring of the next; sets are balanced in size
   int64_t per_leader = tiles0 * p->n_kv_heads;
   int gb = (int)((kTilesPerLaunch + per_leader - 1) / (per_leader > 0 ? per_leader : 1));
-  if (g_overlap_sets > 0) gb = ceil_div(pl->n_leaders, g_overlap_sets);
   if (gb < 1) gb = 1;
   if (gb > pl->n_leaders) gb = pl->n_leaders;
   if (gb > kMaxLayersPerLaunch) gb = kMaxLayersPerLaunch;
@@ -214,27 +190,18 @@ int make_plan(const chunkkv_problem *p, int n_layers, int reuse, Plan *pl) {
   pl->single_ok = single_pass_ok(p->dtype, p->head_dim, rows, p->chunk) ? 1 : 0;
   pl->rows_pad_s = rows > 128 ? 256 : 128;
   pl->n_periods = 0;
-  pl->tpw_s = pl->max_split_s = 1;
+  pl->max_split_s = 1;
   if (pl->single_ok) {
-    int64_t periods = 0;
     for (int b = 0; b < p->batch; ++b) {
       const int np = ceil_div(p->seqlen[b], kSinglePeriodKeys);
-      periods += np;
       if (np > pl->n_periods) pl->n_periods = np;
     }
     // the kernels address E of one problem with 32-bit byte offsets
     if ((int64_t)pl->n_periods * pl->rows_pad_s * 80 >= (int64_t)1 << 32) pl->single_ok = 0;
-    // key-range length in periods: at most kTargetWorkgroupsSingle workgroups, and ranges of at least 16 periods
-    // (so that a workgroup's start-up stays small) unless that would leave fewer workgroups than the chip
-    // holds at once (512)
-    const int64_t total = periods * heads;
-    int64_t floor_p = (total + 511) / 512;
-    if (floor_p > 16) floor_p = 16;
-    pl->tpw_s = (int)((total + kTargetWorkgroupsSingle - 1) / kTargetWorkgroupsSingle);
-    if (pl->tpw_s < floor_p) pl->tpw_s = (int)floor_p;
-    if (pl->tpw_s < 1) pl->tpw_s = 1;
+    // key ranges: single_periods_per_range() periods each, a function of the sequence alone
     for (int b = 0; b < p->batch; ++b) {
-      const int sp = ceil_div(ceil_div(p->seqlen[b], kSinglePeriodKeys), pl->tpw_s);
+      const int np = ceil_div(p->seqlen[b], kSinglePeriodKeys);
+      const int sp = ceil_div(np, single_periods_per_range(np));
       if (sp > pl->max_split_s) pl->max_split_s = sp;
     }
   }
@@ -314,18 +281,18 @@ int run_score(const chunkkv_problem *p, const Plan &pl, const void *const *q, co
       la.n_q_heads = p->n_q_heads; la.n_kv_heads = p->n_kv_heads; la.window = p->window; la.rows_pad = pl.rows_pad;
       { Timed t(kCombine, s); rc = launch_lse_refs(la, ng, nb, s); }
       if (rc) return rc;
-    } else if (pl.single_ok && g_single_pass && !token_imp) {
+    } else if (pl.single_ok && !(p->flags & CHUNKKV_FLAG_TWO_PASS) && !token_imp) {
       // one pass over K: per-(chunk, row) sums and the references they are relative to; then the merge of the
       // range statistics and the weighted row sum in one small kernel
       a.n_periods = pl.n_periods;
       a.e_buf = ws + pl.off_ebuf;
       a.m_period = (float *)(ws + pl.off_mper);
       a.max_split = pl.max_split_s;
-      a.tiles_per_wg = pl.tpw_s;
       a.rows_pad = pl.rows_pad_s;
       int splits = 1;
       for (int i = 0; i < nb; ++i) {
-        const int sp = ceil_div(ceil_div(a.seq.seqlen[i], kSinglePeriodKeys), pl.tpw_s);
+        const int np = ceil_div(a.seq.seqlen[i], kSinglePeriodKeys);
+        const int sp = ceil_div(np, single_periods_per_range(np));
         splits = sp > splits ? sp : splits;
       }
       { Timed t(kStats, s); rc = launch_score_single(p->dtype, a, dim3(splits, nb * p->n_kv_heads, ng), s); }
@@ -363,7 +330,7 @@ int run_topk(const chunkkv_problem *p, const float *chunk_scores, int group0, in
     a.batch0 = b0; a.batch_total = p->batch; a.n_kv_heads = p->n_kv_heads; a.window = p->window; a.chunk = p->chunk;
     a.chunk_scores = chunk_scores; a.score_cap = p->score_cap; a.sel_cap = p->sel_cap;
     a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
-    a.whole_chunks = g_whole_chunks ? 1 : 0;
+    a.whole_chunks = (p->flags & CHUNKKV_FLAG_WHOLE_CHUNKS) ? 1 : 0;
     int rc;
     { Timed t(kTopk, s); rc = launch_topk(a, n_groups, nb, s); }
     if (rc) return rc;
@@ -391,7 +358,7 @@ int run_compact(const chunkkv_problem *p, int l_begin, int n_layers, int reuse, 
       a.out_stride_head = p->out_stride_head; a.out_stride_tok = p->out_stride_tok;
       a.sel_chunk = sel_chunk; a.sel_len = sel_len; a.sel_count = sel_count; a.sel_off = sel_off;
       a.sel_cap = p->sel_cap;
-      a.whole_chunks = g_whole_chunks ? 1 : 0;
+      a.whole_chunks = (p->flags & CHUNKKV_FLAG_WHOLE_CHUNKS) ? 1 : 0;
       int max_entries = 0;
       for (int i = 0; i < nb; ++i) {
         const int nk = a.seq.n_keep[i];
@@ -504,15 +471,8 @@ static int stack_entry(const chunkkv_problem *prob, int32_t n_layers, int32_t re
   float *scores = (float *)(ws + pl.off_scores);
   int32_t *sel_off = (int32_t *)(ws + pl.off_seloff);
 
-  // Algorithm 2: leader layers (l % reuse == 0) are scored and selected set by set on `stream`; the
-  // gather of a set's layers (pure HBM traffic) runs on the helper stream while the next set is
-  // scored (matrix/vector bound), and is joined back into `stream` before the call returns.
-  Overlap *ov = g_overlap_sets > 0 ? overlap_state() : nullptr;
-  if (ov && hipEventRecord(ov->next_event(), s) == hipSuccess) {
-    (void)hipStreamWaitEvent(ov->side, ov->last_event(), 0);  // helper stream starts after the caller's prior work
-  } else {
-    ov = nullptr;
-  }
+  // Algorithm 2: leader layers (l % reuse == 0) are scored and selected, then every layer is gathered with the
+  // selection of its group.  Everything is enqueued on `stream`.
   for (int g0 = 0; g0 < pl.n_leaders; g0 += pl.batch_leaders) {
     const int ng = pl.n_leaders - g0 < pl.batch_leaders ? pl.n_leaders - g0 : pl.batch_leaders;
     const void *qs[kMaxLayersPerLaunch], *ks[kMaxLayersPerLaunch];
@@ -526,18 +486,8 @@ static int stack_entry(const chunkkv_problem *prob, int32_t n_layers, int32_t re
     rc = run_topk(prob, scores, g0, ng, sel_chunk, sel_len, sel_count, sel_off, s);
     if (rc) return rc;
     const int l_begin = g0 * reuse, l_end = (g0 + ng) * reuse < n_layers ? (g0 + ng) * reuse : n_layers;
-    hipStream_t cs = s;
-    if (ov) {
-      if (hipEventRecord(ov->next_event(), s) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
-      if (hipStreamWaitEvent(ov->side, ov->last_event(), 0) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
-      cs = ov->side;
-    }
-    rc = run_compact(prob, l_begin, l_end, reuse, k, v, k_out, v_out, sel_chunk, sel_len, sel_count, sel_off, cs);
+    rc = run_compact(prob, l_begin, l_end, reuse, k, v, k_out, v_out, sel_chunk, sel_len, sel_count, sel_off, s);
     if (rc) return rc;
-  }
-  if (ov) {
-    if (hipEventRecord(ov->next_event(), ov->side) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
-    if (hipStreamWaitEvent(s, ov->last_event(), 0) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
   }
   return CHUNKKV_OK;
 }
@@ -653,27 +603,20 @@ int chunkkv_decode_attention_static(const chunkkv_problem *prob, int32_t compact
   return chunkkv_decode_attention(prob, compacted, kv_len, q, k, v, out, lse, ws, pl.total, stream);
 }
 
-int chunkkv_set_whole_chunks(int32_t enable) {
-  g_whole_chunks = enable != 0;
-  return CHUNKKV_OK;
-}
-
-int chunkkv_set_single_pass(int32_t enable) {
-  g_single_pass = enable != 0;
-  return CHUNKKV_OK;
-}
-
-int chunkkv_set_overlap(int32_t sets) {
-  g_overlap_sets = sets < 0 ? 0 : sets;
-  return CHUNKKV_OK;
-}
-
 int chunkkv_timing_begin(int32_t max_records) {
   if (g_timing.on || max_records < 1) return CHUNKKV_ERR_SHAPE;
-  g_timing.ev = new hipEvent_t[2 * (size_t)max_records];
-  g_timing.kind = new int[max_records];
-  for (int i = 0; i < 2 * max_records; ++i)
-    if (hipEventCreate(&g_timing.ev[i]) != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+  hipEvent_t *ev = new hipEvent_t[2 * (size_t)max_records];
+  int *kind = new int[max_records];
+  for (int i = 0; i < 2 * max_records; ++i) {
+    if (hipEventCreate(&ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+      delete[] ev;
+      delete[] kind;
+      return CHUNKKV_ERR_LAUNCH;
+    }
+  }
+  g_timing.ev = ev;
+  g_timing.kind = kind;
   g_timing.cap = max_records;
   g_timing.used = 0;
   g_timing.on = true;

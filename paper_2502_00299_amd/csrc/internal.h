@@ -45,7 +45,7 @@ struct ScoreArgs {
   float *token_imp;        // [leader][batch_total][Hkv][imp_pitch] or null
   int64_t imp_pitch;
   int32_t fuse_chunks;     // pass 1: 1 = super-tiles hold whole chunks and chunk sums are written
-  // single-pass path (score_single.h): key ranges are whole periods of 160 keys (tiles_per_wg counts periods)
+  // single-pass path (score_single.h): key ranges are single_periods_per_range() whole periods of 160 keys
   int32_t n_periods;       // pitch of e_buf / m_period: max over sequences of ceil(L / 160)
   void *e_buf;             // [problem][n_periods][rows_pad][2 lane halves][80 / c] x 3 bytes: per-(chunk, row) sums of e
   float *m_period;         // [problem][n_periods][rows_pad]  reference those sums are relative to
@@ -115,6 +115,14 @@ __device__ __forceinline__ T pick(const T (&arr)[N], int i) {
 #pragma unroll
   for (int j = 1; j < N; ++j) r = (i == j) ? arr[j] : r;
   return r;
+}
+
+// Single-pass scoring: periods (160 keys) one workgroup walks, for a sequence of n_periods periods.  A function
+// of the sequence alone (about 32 ranges per sequence and kv-head, at least 8 periods each), so the key ranges,
+// and with them every rounding of a score, do not depend on how many layers or sequences share a launch.
+__host__ __device__ inline int single_periods_per_range(int n_periods) {
+  const int p = (n_periods + 31) / 32;
+  return p < 8 ? 8 : p;
 }
 
 // Geometry of the scoring kernels for one (dtype, head_dim, row count).

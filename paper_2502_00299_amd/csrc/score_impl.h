@@ -32,6 +32,7 @@
 // alternate one MFMA with a handful of VALU instructions, so the matrix pipe and the vector ALU of a
 // wavefront work at the same time.  The window queries stay in registers as operand fragments.
 #pragma once
+#include <mutex>
 #include <type_traits>
 
 #include "internal.h"
@@ -402,17 +403,16 @@ __global__ __launch_bounds__(kThreads, ((NQW >= 4 || (DT == CHUNKKV_F32 && HD ==
 
 template <int DT, int HD, int NQW, int WQ>
 int launch_score_cfg(int pass, const ScoreArgs &a, dim3 grid, hipStream_t s) {
-  static bool attr_done[2] = {false, false};
+  static std::once_flag once;
+  static hipError_t attr_rc[2] = {hipSuccess, hipSuccess};
   auto k0 = score_kernel<DT, HD, NQW, WQ, 0>;
   auto k1 = score_kernel<DT, HD, NQW, WQ, 1>;
-  auto kern = pass == 0 ? k0 : k1;
-  if (!attr_done[pass]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kScoreLdsBytes) != hipSuccess)
-      return CHUNKKV_ERR_LAUNCH;
-    attr_done[pass] = true;
-  }
-  hipLaunchKernelGGL(kern, grid, dim3(kThreads), kScoreLdsBytes, s, a);
+  std::call_once(once, [&] {   // both passes, once per process, whichever thread comes first
+    attr_rc[0] = hipFuncSetAttribute(reinterpret_cast<const void *>(k0), hipFuncAttributeMaxDynamicSharedMemorySize, kScoreLdsBytes);
+    attr_rc[1] = hipFuncSetAttribute(reinterpret_cast<const void *>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, kScoreLdsBytes);
+  });
+  if (attr_rc[pass] != hipSuccess) return CHUNKKV_ERR_LAUNCH;
+  hipLaunchKernelGGL(pass == 0 ? k0 : k1, grid, dim3(kThreads), kScoreLdsBytes, s, a);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 

@@ -172,7 +172,8 @@ __global__ __launch_bounds__(256) void single_scores_kernel(ScoreArgs a) {
 
   // ---- references
   {
-    const int nsplit = ((L + kSinglePeriod - 1) / kSinglePeriod + a.tiles_per_wg - 1) / a.tiles_per_wg;
+    const int np_total = (L + kSinglePeriod - 1) / kSinglePeriod, ppr = single_periods_per_range(np_total);
+    const int nsplit = (np_total + ppr - 1) / ppr;
     float m = -1.0e30f, l = 0.f;
     if (tid < nrows) {
       const float2 *ps = a.part_stats + problem * a.max_split * a.rows_pad + tid;

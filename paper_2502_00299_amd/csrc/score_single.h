@@ -115,8 +115,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_single_kernel(ScoreArgs a) 
   const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
 
   const int np_total = (L + kSpPeriod - 1) / kSpPeriod;
-  const int u0 = split * a.tiles_per_wg;
-  const int u1 = u0 + a.tiles_per_wg < np_total ? u0 + a.tiles_per_wg : np_total;
+  const int ppr = single_periods_per_range(np_total);
+  const int u0 = split * ppr;
+  const int u1 = u0 + ppr < np_total ? u0 + ppr : np_total;
   if (u0 >= np_total) return;
   const int np = u1 - u0;               // periods of this workgroup
   const int range0 = u0 * kSpPeriod;    // its first key

@@ -21,7 +21,8 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 }
 
 // Block-wide exclusive scan of one int per thread (1024 threads); returns the exclusive prefix and
-// stores the block total in *total.  s_tmp needs 16 ints.  Ends with a barrier.
+// stores the block total in *total.  s_tmp needs 16 ints.  Starts with a barrier (which also orders it after a
+// previous call's reads of s_tmp) and does not end with one: the caller must not touch s_tmp before its next barrier.
 __device__ __forceinline__ int block_exscan(int x, int *s_tmp, int *total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int inc = x;

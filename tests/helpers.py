@@ -11,6 +11,7 @@ import workloads as W
 from oracle import chunkkv_oracle as orc
 
 REL_TOL = 1e-3     # scores: relative tolerance stated by the task (fp32 accumulation on the GPU)
+DEFAULT_FLAGS = 0   # chunkkv_problem.flags of every problem make_problem builds (set by the scoring_path fixtures)
 
 
 def make_problem(pkg, wl: W.Workload, li: W.LayerInputs, n_keep=None, **kw):
@@ -18,7 +19,7 @@ def make_problem(pkg, wl: W.Workload, li: W.LayerInputs, n_keep=None, **kw):
         n_keep = [W.keep_budget(L, wl.window, wl.keep_pct) for L in li.seqlens]
     return pkg.Problem(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
                        {"f32": pkg.F32, "bf16": pkg.BF16, "f16": pkg.F16}[wl.dtype], list(li.seqlens), list(n_keep),
-                       list(li.kv_base), li.kv_stride_head, li.kv_stride_tok, **kw)
+                       list(li.kv_base), li.kv_stride_head, li.kv_stride_tok, **{"flags": DEFAULT_FLAGS, **kw})
 
 
 def seq_arrays(wl: W.Workload, li: W.LayerInputs, b: int):

@@ -83,6 +83,8 @@ def test_every_storage_type_is_accepted(lib):
     (dict(softmax_scale=-1.0), 2),
     (dict(head_dim=96), 3),
     (dict(dtype=7), 3),
+    (dict(flags=4), 3),                            # unknown flag bit
+    (dict(flags=0x80000000), 3),
     (dict(window=64, n_q_heads=128, n_keep=[100]), 3),   # g*w = 1024 rows > 512
     # K rows of one (sequence, kv-head) must span < 2 GiB: 1.1 M tokens of a packed 8-head bf16 cache do not
     (dict(seqlen=[1_100_000], n_keep=[1000], kv_stride_head=128, kv_stride_tok=8 * 128), 3),
@@ -91,6 +93,22 @@ def test_problem_validation(lib, kw, status):
     p = good(**kw)
     assert score_rc(lib, p) == status
     assert pkg.chunkkv_workspace_bytes(p) == 0
+
+
+def test_flags_travel_per_call(lib):
+    """Selection mode and scoring path are bits of chunkkv_problem.flags: every combination of the known bits
+    passes validation, the flags change no workspace requirement's validity, and the library exports no
+    process-wide switch for them."""
+    assert (pkg.FLAG_WHOLE_CHUNKS, pkg.FLAG_TWO_PASS) == (1, 2)       # the values of the header
+    for flags in (0, pkg.FLAG_WHOLE_CHUNKS, pkg.FLAG_TWO_PASS, pkg.FLAG_WHOLE_CHUNKS | pkg.FLAG_TWO_PASS):
+        p = good(flags=flags)
+        assert pkg.chunkkv_workspace_bytes(p, 4, 2) > 0
+        assert score_rc(lib, p, ws=None) == 4                           # reaches the workspace check
+    header = open(os.path.join(ROOT, "include", "chunkkv.h")).read()
+    assert "CHUNKKV_FLAG_WHOLE_CHUNKS 1u" in header and "CHUNKKV_FLAG_TWO_PASS 2u" in header
+    assert not [n for n in header_functions() if "_set_" in n]
+    for name in ("chunkkv_set_whole_chunks", "chunkkv_set_single_pass", "chunkkv_set_overlap"):
+        assert not hasattr(lib, name) or pytest.fail(f"{name} is still exported")
 
 
 def test_null_pointers_and_workspace(lib):

@@ -147,17 +147,13 @@ def test_decode_over_the_compressed_cache(lib, case, whole):
     travels as kv_len."""
     wl = DECODE_CASES[case]
     li = W.make_layer(wl, 0, DEV)
-    prob = H.make_problem(lib, wl, li)
+    prob = H.make_problem(lib, wl, li, flags=lib.FLAG_WHOLE_CHUNKS if whole else 0)
     B, Hk, Hq, d, w, c = wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim, wl.window, wl.chunk
     sel = alloc_sel(prob)
     k_out = torch.zeros(prob.out_elements(), dtype=li.k.dtype, device=DEV)
     v_out = torch.zeros_like(k_out)
-    lib.chunkkv_set_whole_chunks(whole)
-    try:
-        lib.chunkkv_compress_stack(prob, 1, [li.q], [li.k], [li.v], [k_out], [v_out], *sel,
-                                   torch.empty(lib.chunkkv_workspace_bytes(prob, 1, 1), dtype=torch.uint8, device=DEV))
-    finally:
-        lib.chunkkv_set_whole_chunks(False)
+    lib.chunkkv_compress_stack(prob, 1, [li.q], [li.k], [li.v], [k_out], [v_out], *sel,
+                               torch.empty(lib.chunkkv_workspace_bytes(prob, 1, 1), dtype=torch.uint8, device=DEV))
     torch.cuda.synchronize()
     got = H.read_selection(prob, *sel, 0)
     kv_len = None

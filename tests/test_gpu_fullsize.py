@@ -24,10 +24,10 @@ DEV = "cuda:0"
 @pytest.fixture(params=["single_pass", "two_pass"], autouse=True)
 def scoring_path(request, lib):
     """Every test runs with the single-pass scoring kernel enabled (used where it applies) and with
-    the two-pass kernels forced."""
-    lib.chunkkv_set_single_pass(request.param == "single_pass")
+    the two-pass kernels forced (CHUNKKV_FLAG_TWO_PASS in every problem the helpers build)."""
+    H.DEFAULT_FLAGS = lib.FLAG_TWO_PASS if request.param == "two_pass" else 0
     yield request.param
-    lib.chunkkv_set_single_pass(True)
+    H.DEFAULT_FLAGS = 0
 
 
 def run_stack(lib, wl, R, layers=None):
@@ -111,7 +111,8 @@ def test_stack_128k_32_layers_reuse2(lib):
     layers, prob, sel, k_out, v_out = run_stack(lib, wl, 2)
     check_structure_everywhere(wl, prob, sel, 2)
     check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, 2)
-    check_sampled_selections(lib, wl, layers, prob, sel, 2, [(0, 0, 0), (7, 0, 5), (15, 0, 7)])
+    # 16 of the 128 (group, kv-head) selections against the oracle: every group once, every head twice
+    check_sampled_selections(lib, wl, layers, prob, sel, 2, [(g, 0, (3 * g + g // 8) % 8) for g in range(16)])
     # chunk scores of two heads of one leader layer at full length
     li = layers[14]
     cs = torch.zeros((1, wl.n_kv_heads, prob.score_cap), dtype=torch.float32, device=DEV)
@@ -138,22 +139,42 @@ def test_stack_32k_32_layers(lib, R):
     check_sampled_selections(lib, wl, layers, prob, sel, R, [(0, 0, 3), (G // 2, 0, 0), (G - 1, 0, 7)])
 
 
-def test_stack_128k_keep20(lib):
-    wl = W.get_workload("llama8b_128k_stack").with_(keep_pct=20, n_layers=8)
-    print("workload", wl.name, "20% 8 layers R=2", flush=True)
+def test_stack_128k_keep20(lib, scoring_path):
+    """The long-context configuration at its second budget: all 32 layers, keep 20 %, R = 2."""
+    if scoring_path == "two_pass":
+        pytest.skip("the budget only changes selection and gather; one scoring path is enough at this size")
+    wl = W.get_workload("llama8b_128k_stack").with_(keep_pct=20)
+    print("workload", wl.name, "20% 32 layers R=2", flush=True)
     layers, prob, sel, k_out, v_out = run_stack(lib, wl, 2)
     check_structure_everywhere(wl, prob, sel, 2)
     check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, 2)
-    check_sampled_selections(lib, wl, layers, prob, sel, 2, [(3, 0, 2)])
+    check_sampled_selections(lib, wl, layers, prob, sel, 2, [(0, 0, 6), (5, 0, 2), (10, 0, 4), (15, 0, 1)])
 
 
-@pytest.mark.parametrize("chunk,pct,R", [(5, 10, 1), (10, 20, 2), (20, 30, 3), (5, 30, 2), (10, 10, 3), (20, 20, 1)])
-def test_ragged_batch_sweep(lib, chunk, pct, R):
-    # batch of 8 ragged sequences (4096..65536 tokens), 28 q / 4 kv heads, packed [sum L][Hkv][d];
-    # 6 of the 28 layers keep the run short, the launch shapes per layer are those of the full stack
+_ragged_layers = {}
+
+
+def ragged_layers(n_layers):
+    """The first layers of the ragged workload, generated once per session (chunk size, budget and reuse depth
+    do not enter the inputs)."""
+    if n_layers not in _ragged_layers:
+        wl = W.get_workload("ragged_b8").with_(n_layers=n_layers)
+        _ragged_layers[n_layers] = [W.make_layer(wl, l, DEV) for l in range(n_layers)]
+    return _ragged_layers[n_layers]
+
+
+@pytest.mark.parametrize("R", [1, 2, 3])
+@pytest.mark.parametrize("pct", [10, 20, 30])
+@pytest.mark.parametrize("chunk", [5, 10, 20])
+def test_ragged_batch_sweep(lib, chunk, pct, R, scoring_path):
+    if scoring_path == "two_pass" and R != 2:
+        pytest.skip("the two-pass kernels run the R = 2 third of the sweep")
+    # batch of 8 ragged sequences (4096..65536 tokens), 28 q / 4 kv heads, packed [sum L][Hkv][d]: all 27
+    # (chunk size, budget, reuse depth) combinations of the sweep; 6 of the 28 layers keep a run short, the
+    # launch shapes per layer are those of the full stack
     wl = W.get_workload("ragged_b8").with_(chunk=chunk, keep_pct=pct, n_layers=6)
     print("workload", wl.name, f"c={chunk} keep={pct}% R={R} L={wl.seqlens}", flush=True)
-    layers, prob, sel, k_out, v_out = run_stack(lib, wl, R)
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, R, ragged_layers(6))
     check_structure_everywhere(wl, prob, sel, R)
     check_gather_everywhere(wl, layers, prob, sel, k_out, v_out, R)
     short = int(np.argmin(wl.seqlens))

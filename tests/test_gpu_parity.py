@@ -18,10 +18,10 @@ DEV = "cuda:0"
 @pytest.fixture(params=["single_pass", "two_pass"], autouse=True)
 def scoring_path(request, lib):
     """Every test runs with the single-pass scoring kernel enabled (used where it applies) and with
-    the two-pass kernels forced."""
-    lib.chunkkv_set_single_pass(request.param == "single_pass")
+    the two-pass kernels forced (CHUNKKV_FLAG_TWO_PASS in every problem the helpers build)."""
+    H.DEFAULT_FLAGS = lib.FLAG_TWO_PASS if request.param == "two_pass" else 0
     yield request.param
-    lib.chunkkv_set_single_pass(True)
+    H.DEFAULT_FLAGS = 0
 
 
 def small(name, **kw):
@@ -347,8 +347,9 @@ def test_score_lse_matches_oracle(lib, case):
         assert worst <= H.REL_TOL
 
 
-def test_compress_stack_lse_matches_oracle(lib):
-    wl, R = small("llama8b_32k_stack", seqlens=(4096,), n_spans=(20,), n_layers=5), 2
+@pytest.mark.parametrize("R", [2, 3])
+def test_compress_stack_lse_matches_oracle(lib, R):
+    wl = small("llama8b_32k_stack", seqlens=(4096,), n_spans=(20,), n_layers=5)
     N, B, Hk = wl.n_layers, wl.batch, wl.n_kv_heads
     layers = [W.make_layer(wl, l, DEV) for l in range(N)]
     prob = H.make_problem(lib, wl, layers[0])
@@ -607,10 +608,12 @@ def test_random_shapes_match_oracle(lib, idx):
 
 # ------------------------------------------------------------------ whole-chunk selection mode (Algorithm 3 as printed)
 @pytest.fixture
-def whole_chunks(lib):
-    lib.chunkkv_set_whole_chunks(True)
+def whole_chunks(lib, scoring_path):
+    """CHUNKKV_FLAG_WHOLE_CHUNKS in every problem the helpers build (beside the scoring-path flag)."""
+    before = H.DEFAULT_FLAGS
+    H.DEFAULT_FLAGS = before | lib.FLAG_WHOLE_CHUNKS
     yield
-    lib.chunkkv_set_whole_chunks(False)
+    H.DEFAULT_FLAGS = before
 
 
 @pytest.mark.parametrize("case", ["bf16_8k", "bf16_rows96", "bf16_P_lt_chunk", "tiny_f32"])
