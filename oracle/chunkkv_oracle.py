@@ -36,6 +36,16 @@ Readings taken where the paper is silent or its listings disagree
       attention of ONE new query token per head over every token of K', V':
       softmax(q K'^T / sqrt(d)) V', query head i reading kv-head i // g; the
       paper does not restate it.
+  R17 A chunk size per layer group (the hybrid ablation of Section 4.6 runs a different setting in the bottom
+      and in the top half of the layers; chunk size 1 is token-level selection): every layer of a reuse group
+      uses its group's chunk size, the budget is the same token count everywhere.
+  R18 The two quality metrics of Appendix A.1 (the paper names them, gives no formula):
+      KV cache L1 loss = sum |X - X~| / sum |X| over all K and V entries of a layer, X~ being the cache with
+      the dropped tokens zeroed, i.e. the share of the cache's absolute mass that sits in dropped tokens
+      (0 when everything is kept; about 0.9 at a 10 % budget, the range the paper's table shows);
+      attention cosine similarity = cosine between the attention distribution of the decoding query over the
+      full cache and the one over the kept tokens (scattered to their positions, zero elsewhere), per query
+      head, averaged over the heads of the layer.
   R13 Caller-supplied row normalisation (the variant for callers that run behind
       a fused attention kernel): the natural log-sum-exp of the scaled logits
       over the keys the row sees, window keys up to its own position included.
@@ -54,6 +64,10 @@ the Jaccard similarity is pinned on hand-counted overlaps; decode attention
 is pinned on one token (returns its value row), identical keys (mean of the
 value rows), a dominant key, a library scaled-dot-product attention, explicit
 loops, a library logsumexp, and the rule that merges two partial results;
+the quality metrics are pinned on identity (everything kept: loss 0, cosine 1), on closed forms for
+constant-magnitude caches (loss = dropped share of tokens) and identical keys (cosine = sqrt(kept / all)),
+on a hand-computed three-token example and on the identity cosine^2 = sum of squared full-cache
+probabilities over the kept tokens / over all tokens;
 the cache-size formula reproduces the worked example printed beside Eq. 1
 (tests/golden/eq1_kv_cache_memory.json) and the reuse speed-up model its stated limit.
 The paper prints no worked numeric example of this path, so parity on real
@@ -306,25 +320,77 @@ def compress_layer(q_obs, k, v, w: int, c: int, n_keep: int, scale: Optional[flo
     return ko, vo, sel, cs
 
 
-def compress_stack(q_obs_layers, k_layers, v_layers, w: int, c: int, n_keep: int, reuse: int,
+def compress_stack(q_obs_layers, k_layers, v_layers, w: int, c, n_keep: int, reuse: int,
                    scale: Optional[float] = None):
     """Algorithm 2: layer l recomputes its selection when l mod reuse == 0 and
     otherwise gathers with the selection of layer floor(l/reuse)*reuse.
 
     q_obs_layers[l] may be None for layers that do not recompute.
+    c: one chunk size, or one per reuse group (reading R17: group l // reuse scores, selects and gathers with
+    its own chunk size; the budget n_keep is the same token count everywhere).
     Returns (list of K', list of V', list of selections per reuse group).
     """
     assert reuse >= 1
     P = k_layers[0].shape[1] - w
+    n_groups = (len(k_layers) + reuse - 1) // reuse
+    cs_group = [int(c)] * n_groups if np.isscalar(c) else [int(x) for x in c]
+    assert len(cs_group) == n_groups
     store = {}
     k_out, v_out, groups = [], [], []
     for l in range(len(k_layers)):
+        cg = cs_group[l // reuse]
         if l % reuse == 0:
-            cs, _ = score(q_obs_layers[l], k_layers[l], w, c, scale)
-            store[l] = [chunk_topk(cs[h], P, c, n_keep) for h in range(k_layers[l].shape[0])]
+            cs, _ = score(q_obs_layers[l], k_layers[l], w, cg, scale)
+            store[l] = [chunk_topk(cs[h], P, cg, n_keep) for h in range(k_layers[l].shape[0])]
             groups.append(store[l])
         sel = store[(l // reuse) * reuse]
-        ko, vo = compact(k_layers[l], v_layers[l], [s[0] for s in sel], [s[1] for s in sel], w, c)
+        ko, vo = compact(k_layers[l], v_layers[l], [s[0] for s in sel], [s[1] for s in sel], w, cg)
         k_out.append(ko)
         v_out.append(vo)
     return k_out, v_out, groups
+
+
+def kv_l1_loss(k: np.ndarray, v: np.ndarray, kept: Sequence[np.ndarray]) -> float:
+    """KV cache L1 loss of one layer of one sequence (Appendix A.1, reading R18).
+
+    k, v: [Hkv][L][d]; kept[h]: token indices kv-head h keeps (window included).  The compressed cache is
+    compared entry by entry with the full one, dropped tokens counting as zeros:
+    sum |X - X~| / sum |X| over K and V."""
+    k, v = widen(k), widen(v)
+    num = den = 0.0
+    for h in range(k.shape[0]):
+        mask = np.zeros(k.shape[1], dtype=bool)
+        mask[np.asarray(kept[h], dtype=np.int64)] = True
+        for x in (k[h], v[h]):
+            x_tilde = np.where(mask[:, None], x, 0.0)
+            num += np.abs(x - x_tilde).sum()
+            den += np.abs(x).sum()
+    return num / den if den > 0 else 0.0
+
+
+def attention_cosine(q: np.ndarray, k: np.ndarray, kept: Sequence[np.ndarray], scale: Optional[float] = None) -> np.ndarray:
+    """Attention cosine similarity of one layer of one sequence (Appendix A.1, reading R18), per query head.
+
+    q: [Hq][d], the decoding query; k: [Hkv][L][d]; kept[h]: token indices kv-head h keeps.  For query head i
+    (kv-head i // g): p = softmax over all L tokens, p~ = softmax over the kept tokens, written at their
+    positions in a vector of zeros; returns cos(p, p~) = p . p~ / (|p| |p~|) for every head."""
+    q, k = widen(q), widen(k)
+    Hq, d = q.shape
+    Hkv, L, _ = k.shape
+    g = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros(Hq)
+    for i in range(Hq):
+        h = i // g
+        s = (k[h] @ q[i]) * scale
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        idx = np.asarray(kept[h], dtype=np.int64)
+        pc = np.zeros(L)
+        if idx.size:
+            e = np.exp(s[idx] - s[idx].max())
+            pc[idx] = e / e.sum()
+        nrm = math.sqrt((p * p).sum()) * math.sqrt((pc * pc).sum())
+        out[i] = (p * pc).sum() / nrm if nrm > 0 else 0.0
+    return out

@@ -285,6 +285,37 @@ def test_keep_everything_is_identity_through_the_stack():
         assert np.array_equal(ko[l], ks[l]) and np.array_equal(vo[l], vs[l])
 
 
+def test_per_group_chunk_sizes_equal_separate_stacks():
+    # reading R17: a stack with a chunk size per reuse group is the concatenation of uniform stacks over the
+    # runs of groups; chunk size 1 in a group is plain token-level top-k there
+    qs, ks, vs = _stack(15, 7)
+    w, n_keep, R = 4, 20, 2
+    cs = [6, 1, 9, 3]
+    ko, vo, groups = orc.compress_stack([q if l % R == 0 else None for l, q in enumerate(qs)],
+                                        ks, vs, w, cs, n_keep, R)
+    assert len(groups) == 4
+    for g, c in enumerate(cs):
+        lo, hi = g * R, min(7, (g + 1) * R)
+        k1, v1, g1 = orc.compress_stack([qs[lo]] + [None] * (hi - lo - 1), ks[lo:hi], vs[lo:hi], w, c, n_keep, R)
+        for l in range(lo, hi):
+            assert np.array_equal(ko[l], k1[l - lo]) and np.array_equal(vo[l], v1[l - lo])
+            assert ko[l].shape == (2, n_keep + w, 8)
+    # the token-level group keeps exactly the n_keep highest-importance prefix tokens of its leader
+    _, imp = orc.score(qs[2], ks[2], w, 1)
+    for h in range(2):
+        top = np.sort(np.argsort(-imp[h], kind="stable")[:n_keep])
+        assert np.array_equal(np.sort(groups[1][h][0]), top)
+        assert np.all(groups[1][h][1] == 1)
+
+
+def test_uniform_chunk_list_equals_scalar_chunk():
+    qs, ks, vs = _stack(16, 5)
+    a = orc.compress_stack(qs, ks, vs, 4, 6, 20, 2)
+    b = orc.compress_stack(qs, ks, vs, 4, [6, 6, 6], 20, 2)
+    for x, y in zip(a[0] + a[1], b[0] + b[1]):
+        assert np.array_equal(x, y)
+
+
 def test_planted_span_is_found_when_strong():
     # a strongly planted span must be among the kept chunks (sanity of the whole path)
     r = rng(14)
@@ -522,3 +553,73 @@ def test_reuse_speedup_model_limits():
     # a gather as expensive as a full compression gains nothing; in between the closed form by hand
     assert math.isclose(orc.reuse_speedup(32, 2, 1.0, 1.0), 1.0)
     assert math.isclose(orc.reuse_speedup(32, 2, 1.0, 0.287), 32 / (16 + 16 * 0.287))
+
+
+# ----------------------------------------------------------------- quality metrics (Appendix A.1, reading R18)
+def test_quality_metrics_keep_everything_is_lossless():
+    r = rng(40)
+    k, v, q = r.standard_normal((2, 30, 8)), r.standard_normal((2, 30, 8)), r.standard_normal((4, 8))
+    kept = [np.arange(30), np.arange(30)]
+    assert orc.kv_l1_loss(k, v, kept) == 0.0
+    assert np.allclose(orc.attention_cosine(q, k, kept), 1.0, rtol=0, atol=1e-15)
+
+
+def test_l1_loss_of_constant_magnitude_cache_is_dropped_token_share():
+    # every entry has magnitude 1: the dropped share of absolute mass is the dropped share of (head, token) pairs
+    r = rng(41)
+    k = np.sign(r.standard_normal((3, 40, 8)))
+    v = np.sign(r.standard_normal((3, 40, 8)))
+    kept = [np.arange(0, 40, 2), np.arange(10), np.arange(40)]          # 20, 10, 40 kept of 40 each
+    assert orc.kv_l1_loss(k, v, kept) == pytest.approx(1.0 - 70.0 / 120.0, rel=1e-15)
+
+
+def test_l1_loss_hand_example():
+    # one head, three tokens, d=1: |K| = 1,2,3 and |V| = 4,0,2; dropping token 1 loses 2 of 12
+    k = np.array([[[1.0], [-2.0], [3.0]]])
+    v = np.array([[[-4.0], [0.0], [2.0]]])
+    assert orc.kv_l1_loss(k, v, [np.array([0, 2])]) == pytest.approx(2.0 / 12.0, rel=1e-15)
+    assert orc.kv_l1_loss(k, v, [np.array([1])]) == pytest.approx(10.0 / 12.0, rel=1e-15)
+    assert orc.kv_l1_loss(k, v, [np.array([], dtype=np.int64)]) == 1.0
+
+
+def test_attention_cosine_of_identical_keys_is_sqrt_of_kept_share():
+    # uniform attention over L tokens against uniform over n kept ones: cos = (n/(L n)) / (1/sqrt(L) 1/sqrt(n))
+    r = rng(42)
+    L, d = 50, 8
+    k = np.broadcast_to(r.standard_normal((2, 1, d)), (2, L, d)).copy()
+    q = r.standard_normal((4, d))
+    kept = [np.arange(0, 50, 5), np.arange(25)]
+    cos = orc.attention_cosine(q, k, kept)
+    assert np.allclose(cos[:2], math.sqrt(10 / 50), rtol=1e-13)
+    assert np.allclose(cos[2:], math.sqrt(25 / 50), rtol=1e-13)
+
+
+def test_attention_cosine_hand_example_pins_scale_and_head_map():
+    # d=1, scale given: scores of head 0 are s = ln 1, ln 2, ln 3 -> p = (1,2,3)/6; keeping tokens {1,2}:
+    # p~ = (0,2,3)/5, cos = 13 / (sqrt(14) sqrt(13)).  Query head 1 reads kv-head 1 (g = 1) whose scores are
+    # ln 4, ln 1, ln 1 with token 0 kept alone: cos = 4 / sqrt(18).
+    k = np.array([[[math.log(1.0)], [math.log(2.0)], [math.log(3.0)]],
+                  [[math.log(4.0)], [0.0], [0.0]]])
+    q = np.array([[2.0], [2.0]])
+    cos = orc.attention_cosine(q, k, [np.array([1, 2]), np.array([0])], scale=0.5)
+    assert cos[0] == pytest.approx(13.0 / math.sqrt(14.0 * 13.0), rel=1e-14)
+    assert cos[1] == pytest.approx(4.0 / math.sqrt(18.0), rel=1e-14)
+    # grouped heads: two query heads share kv-head 0 and see the same kept set
+    cos2 = orc.attention_cosine(np.array([[2.0], [2.0]]), k[:1], [np.array([1, 2])], scale=0.5)
+    assert cos2[0] == cos2[1] == cos[0]
+
+
+def test_attention_cosine_squared_is_kept_share_of_squared_probabilities():
+    # p~ is p restricted to the kept set and renormalised, so cos^2 = sum_kept p^2 / sum_all p^2
+    r = rng(43)
+    Hq, Hkv, L, d = 6, 2, 70, 16
+    q, k = r.standard_normal((Hq, d)) * 2, r.standard_normal((Hkv, L, d))
+    kept = [np.sort(r.choice(L, 20, replace=False)) for _ in range(Hkv)]
+    cos = orc.attention_cosine(q, k, kept)
+    for i in range(Hq):
+        h = i // 3
+        p = softmax((k[h] @ q[i]) / math.sqrt(d))
+        assert cos[i] ** 2 == pytest.approx((p[kept[h]] ** 2).sum() / (p ** 2).sum(), rel=1e-12)
+    # dropping more tokens never raises the similarity
+    fewer = [x[:10] for x in kept]
+    assert np.all(orc.attention_cosine(q, k, fewer) <= cos + 1e-15)
