@@ -160,11 +160,38 @@ int chunkkv_compress_stack_lse(const chunkkv_problem *prob, int32_t n_layers, in
  *   sel_chunk, sel_len, sel_count   the arrays of chunkkv_compress_stack ([G][B][Hkv][sel_cap], [G][B][Hkv]);
  *                    group layer / reuse is written (leader layers) or read (the others)
  *   workspace        chunkkv_workspace_bytes(prob, 1, 1) bytes; nothing in it has to survive between calls
+ * prob->chunk may differ between reuse groups (Section 4.6 runs different chunk sizes in different layers), but
+ * every layer of one group must be passed the chunk size of the group's leader: the selection arrays store
+ * chunk indices, the library keeps no record of the grid they refer to, and a follower called with another
+ * chunk size gathers other tokens without any error.  chunkkv_compress_stack_hybrid takes the table of chunk
+ * sizes once and cannot get this wrong.
  * Results are those of chunkkv_compress_stack over the same layers.  Errors as there.                       */
 int chunkkv_compress_layer(const chunkkv_problem *prob, int32_t layer, int32_t reuse, const void *q_obs,
                            const float *lse, const void *k, const void *v, void *k_out, void *v_out,
                            int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, void *workspace,
                            size_t workspace_bytes, void *stream);
+
+/* Algorithm 2 with a chunk size per reuse group (the hybrid setting among the chunk-size ablations of
+ * Section 4.6; chunk size 1 in a group is token-level selection there).  Group G = l / reuse scores, selects
+ * and gathers with chunk_per_group[G]; prob->chunk is ignored; the budget n_keep[b] is the same token count in
+ * every group.  Implemented as chunkkv_compress_stack over each run of consecutive groups with one chunk size,
+ * so the results of a group are those of chunkkv_compress_stack with that chunk size.
+ *   chunk_per_group  HOST int32 [ceil(n_layers / reuse)], every entry >= 1
+ *   lse              NULL, or as in chunkkv_compress_stack_lse
+ *   sel_chunk, sel_len, sel_count   as in chunkkv_compress_stack; group G's entries count chunks of
+ *                    chunk_per_group[G] tokens.  prob->sel_cap and prob->score_cap must hold for the smallest
+ *                    chunk size in the table.
+ *   workspace        chunkkv_workspace_bytes_hybrid(...) bytes (0 = invalid arguments): the largest need of
+ *                    any chunk size in the table
+ * All arguments are checked for every run before the first launch.  Errors as for chunkkv_compress_stack;
+ * CHUNKKV_ERR_NULL for a missing table, CHUNKKV_ERR_SHAPE for an entry < 1 or a capacity too small for it.    */
+size_t chunkkv_workspace_bytes_hybrid(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse,
+                                      const int32_t *chunk_per_group);
+int chunkkv_compress_stack_hybrid(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse,
+                                  const int32_t *chunk_per_group, const void *const *q_obs,
+                                  const void *const *k, const void *const *v, const float *const *lse,
+                                  void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
+                                  int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Adjacent-group Jaccard similarity of the kept token sets, the diagnostic that motivates layer-wise index
  * reuse (Section 3.3 and the similarity tables of Appendix B.2): for g = 0..n_groups-2

@@ -21,7 +21,7 @@ F32, BF16, F16 = 0, 1, 2
 FLAG_WHOLE_CHUNKS, FLAG_TWO_PASS = 1, 2     # chunkkv_problem.flags
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
-           "chunkkv_compress_layer", "chunkkv_jaccard", "chunkkv_decode_workspace_bytes", "chunkkv_decode_attention",
+           "chunkkv_compress_layer", "chunkkv_workspace_bytes_hybrid", "chunkkv_compress_stack_hybrid", "chunkkv_jaccard", "chunkkv_decode_workspace_bytes", "chunkkv_decode_attention",
            "chunkkv_decode_attention_static",
            "chunkkv_timing_begin",
            "chunkkv_timing_end")
@@ -152,6 +152,12 @@ def load_library(path: Optional[str] = None):
     lib.chunkkv_compress_layer.restype = C.c_int
     lib.chunkkv_compress_layer.argtypes = [C.POINTER(_CProblem), C.c_int32, C.c_int32, vp, f32p, vp, vp, vp, vp,
                                            i32p, i32p, i32p, vp, C.c_size_t, vp]
+    lib.chunkkv_workspace_bytes_hybrid.restype = C.c_size_t
+    lib.chunkkv_workspace_bytes_hybrid.argtypes = [C.POINTER(_CProblem), C.c_int32, C.c_int32, i32p]
+    lib.chunkkv_compress_stack_hybrid.restype = C.c_int
+    lib.chunkkv_compress_stack_hybrid.argtypes = [C.POINTER(_CProblem), C.c_int32, C.c_int32, i32p, C.POINTER(vp),
+                                                  C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                                  C.POINTER(vp), i32p, i32p, i32p, vp, C.c_size_t, vp]
     lib.chunkkv_jaccard.restype = C.c_int
     lib.chunkkv_jaccard.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, i32p, i32p, f32p, vp]
     lib.chunkkv_decode_workspace_bytes.restype = C.c_size_t
@@ -258,6 +264,31 @@ def chunkkv_compress_layer(prob: Problem, layer: int, reuse: int, q_obs, lse, k,
         _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
         "chunkkv_compress_layer")
+
+
+def _chunk_table(chunk_per_group):
+    return None if chunk_per_group is None else (C.c_int32 * len(chunk_per_group))(*[int(c) for c in chunk_per_group])
+
+
+def chunkkv_workspace_bytes_hybrid(prob: Problem, n_layers: int, reuse: int, chunk_per_group) -> int:
+    return int(load_library().chunkkv_workspace_bytes_hybrid(C.byref(prob.as_c()), n_layers, reuse,
+                                                             _chunk_table(chunk_per_group)))
+
+
+def chunkkv_compress_stack_hybrid(prob: Problem, reuse: int, chunk_per_group, q_obs: Sequence, k: Sequence,
+                                  v: Sequence, lse, k_out: Sequence, v_out: Sequence, sel_chunk, sel_len, sel_count,
+                                  workspace, stream=None) -> None:
+    n = len(k)
+    cp = prob.as_c()
+
+    def table(ts):
+        return None if ts is None else (C.c_void_p * n)(*[None if t is None else t.data_ptr() for t in ts])
+
+    _check(load_library().chunkkv_compress_stack_hybrid(
+        C.byref(cp), n, reuse, _chunk_table(chunk_per_group), table(q_obs), table(k), table(v), table(lse),
+        table(k_out), table(v_out), _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
+        "chunkkv_compress_stack_hybrid")
 
 
 def chunkkv_jaccard(prob: Problem, n_groups: int, sel_chunk, sel_len, sel_count, jaccard, stream=None) -> None:

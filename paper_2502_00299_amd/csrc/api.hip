@@ -379,6 +379,28 @@ int run_compact(const chunkkv_problem *p, int l_begin, int n_layers, int reuse, 
 
 using namespace ckv;
 
+// Runs of consecutive reuse groups with one chunk size; fn(problem with that chunk, first group, end group).
+template <typename F>
+static int for_chunk_runs(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const int32_t *chunk_per_group,
+                          F fn) {
+  if (!prob) return CHUNKKV_ERR_NULL;
+  if (!chunk_per_group) return CHUNKKV_ERR_NULL;
+  if (n_layers < 1 || reuse < 1) return CHUNKKV_ERR_SHAPE;
+  const int n_groups = ceil_div(n_layers, reuse);
+  for (int g0 = 0; g0 < n_groups;) {
+    int g1 = g0 + 1;
+    while (g1 < n_groups && chunk_per_group[g1] == chunk_per_group[g0]) ++g1;
+    chunkkv_problem run = *prob;
+    run.chunk = chunk_per_group[g0];
+    int rc = check_problem(&run, true);
+    if (rc) return rc;
+    rc = fn(run, g0, g1);
+    if (rc) return rc;
+    g0 = g1;
+  }
+  return CHUNKKV_OK;
+}
+
 extern "C" {
 
 const char *chunkkv_status_string(int status) {
@@ -446,12 +468,10 @@ int chunkkv_compact(const chunkkv_problem *prob, const void *k, const void *v, c
                      (hipStream_t)stream);
 }
 
-static int stack_entry(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,
-                       const void *const *k, const void *const *v, const float *const *lse, bool with_lse,
-                       void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
-                       int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream) {
-  int rc = check_problem(prob, true);
-  if (rc) return rc;
+static int check_stack_pointers(int32_t n_layers, int32_t reuse, const void *const *q_obs, const void *const *k,
+                                const void *const *v, const float *const *lse, bool with_lse, void *const *k_out,
+                                void *const *v_out, const int32_t *sel_chunk, const int32_t *sel_len,
+                                const int32_t *sel_count) {
   if (n_layers < 1 || reuse < 1) return CHUNKKV_ERR_SHAPE;
   if (!q_obs || !k || !v || !k_out || !v_out || !sel_chunk || !sel_len || !sel_count) return CHUNKKV_ERR_NULL;
   if (with_lse && !lse) return CHUNKKV_ERR_NULL;
@@ -462,26 +482,27 @@ static int stack_entry(const chunkkv_problem *prob, int32_t n_layers, int32_t re
     if (misaligned(k[l]) || misaligned(v[l]) || misaligned(k_out[l]) || misaligned(v_out[l])) return CHUNKKV_ERR_SHAPE;
     if (l % reuse == 0 && misaligned(q_obs[l])) return CHUNKKV_ERR_SHAPE;
   }
-  Plan pl;
-  rc = make_plan(prob, n_layers, reuse, &pl);
-  if (rc) return rc;
-  if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
-  char *ws = (char *)workspace;
-  hipStream_t s = (hipStream_t)stream;
+  return CHUNKKV_OK;
+}
+
+// Algorithm 2 over the reuse groups [g_begin, g_end) of a stack of n_layers layers: leader layers (l % reuse == 0)
+// are scored and selected, then every layer of these groups is gathered with the selection of its group.
+// `pl` is the plan of the whole stack for prob->chunk.  Everything is enqueued on `s`.
+static int stack_groups(const chunkkv_problem *prob, const Plan &pl, int g_begin, int g_end, int32_t n_layers,
+                        int32_t reuse, const void *const *q_obs, const void *const *k, const void *const *v,
+                        const float *const *lse, bool with_lse, void *const *k_out, void *const *v_out,
+                        int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count, char *ws, hipStream_t s) {
   float *scores = (float *)(ws + pl.off_scores);
   int32_t *sel_off = (int32_t *)(ws + pl.off_seloff);
-
-  // Algorithm 2: leader layers (l % reuse == 0) are scored and selected, then every layer is gathered with the
-  // selection of its group.  Everything is enqueued on `stream`.
-  for (int g0 = 0; g0 < pl.n_leaders; g0 += pl.batch_leaders) {
-    const int ng = pl.n_leaders - g0 < pl.batch_leaders ? pl.n_leaders - g0 : pl.batch_leaders;
+  for (int g0 = g_begin; g0 < g_end; g0 += pl.batch_leaders) {
+    const int ng = g_end - g0 < pl.batch_leaders ? g_end - g0 : pl.batch_leaders;
     const void *qs[kMaxLayersPerLaunch], *ks[kMaxLayersPerLaunch];
     const float *ls[kMaxLayersPerLaunch];
     for (int i = 0; i < ng; ++i) {
       qs[i] = q_obs[(g0 + i) * reuse]; ks[i] = k[(g0 + i) * reuse];
       ls[i] = with_lse ? lse[(g0 + i) * reuse] : nullptr;
     }
-    rc = run_score(prob, pl, qs, ks, with_lse ? ls : nullptr, ng, g0, scores, nullptr, 0, ws, s);
+    int rc = run_score(prob, pl, qs, ks, with_lse ? ls : nullptr, ng, g0, scores, nullptr, 0, ws, s);
     if (rc) return rc;
     rc = run_topk(prob, scores, g0, ng, sel_chunk, sel_len, sel_count, sel_off, s);
     if (rc) return rc;
@@ -490,6 +511,62 @@ static int stack_entry(const chunkkv_problem *prob, int32_t n_layers, int32_t re
     if (rc) return rc;
   }
   return CHUNKKV_OK;
+}
+
+static int stack_entry(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,
+                       const void *const *k, const void *const *v, const float *const *lse, bool with_lse,
+                       void *const *k_out, void *const *v_out, int32_t *sel_chunk, int32_t *sel_len,
+                       int32_t *sel_count, void *workspace, size_t workspace_bytes, void *stream) {
+  int rc = check_problem(prob, true);
+  if (rc) return rc;
+  rc = check_stack_pointers(n_layers, reuse, q_obs, k, v, lse, with_lse, k_out, v_out, sel_chunk, sel_len, sel_count);
+  if (rc) return rc;
+  Plan pl;
+  rc = make_plan(prob, n_layers, reuse, &pl);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
+  return stack_groups(prob, pl, 0, pl.n_leaders, n_layers, reuse, q_obs, k, v, lse, with_lse, k_out, v_out, sel_chunk,
+                      sel_len, sel_count, (char *)workspace, (hipStream_t)stream);
+}
+
+size_t chunkkv_workspace_bytes_hybrid(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse,
+                                      const int32_t *chunk_per_group) {
+  size_t need = 0;
+  const int rc = for_chunk_runs(prob, n_layers, reuse, chunk_per_group, [&](const chunkkv_problem &run, int, int) {
+    Plan pl;
+    const int r = make_plan(&run, n_layers, reuse, &pl);
+    if (r) return r;
+    need = pl.total > need ? pl.total : need;
+    return (int)CHUNKKV_OK;
+  });
+  return rc ? 0 : need;
+}
+
+int chunkkv_compress_stack_hybrid(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse,
+                                  const int32_t *chunk_per_group, const void *const *q_obs, const void *const *k,
+                                  const void *const *v, const float *const *lse, void *const *k_out,
+                                  void *const *v_out, int32_t *sel_chunk, int32_t *sel_len, int32_t *sel_count,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  // everything is checked for every run before the first launch
+  const size_t need = chunkkv_workspace_bytes_hybrid(prob, n_layers, reuse, chunk_per_group);
+  if (need == 0) {
+    const int rc = for_chunk_runs(prob, n_layers, reuse, chunk_per_group, [&](const chunkkv_problem &run, int, int) {
+      Plan pl;
+      return make_plan(&run, n_layers, reuse, &pl);
+    });
+    return rc ? rc : CHUNKKV_ERR_SHAPE;
+  }
+  const bool with_lse = lse != nullptr;
+  int rc = check_stack_pointers(n_layers, reuse, q_obs, k, v, lse, with_lse, k_out, v_out, sel_chunk, sel_len, sel_count);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < need) return CHUNKKV_ERR_WORKSPACE;
+  return for_chunk_runs(prob, n_layers, reuse, chunk_per_group, [&](const chunkkv_problem &run, int g0, int g1) {
+    Plan pl;
+    const int r = make_plan(&run, n_layers, reuse, &pl);
+    if (r) return r;
+    return stack_groups(&run, pl, g0, g1, n_layers, reuse, q_obs, k, v, lse, with_lse, k_out, v_out, sel_chunk, sel_len,
+                        sel_count, (char *)workspace, (hipStream_t)stream);
+  });
 }
 
 int chunkkv_compress_stack(const chunkkv_problem *prob, int32_t n_layers, int32_t reuse, const void *const *q_obs,

@@ -183,6 +183,31 @@ def test_layer_and_jaccard_argument_checks(lib):
     assert lib.chunkkv_jaccard(C.byref(cp), 3, FAKE, FAKE, FAKE, None, None) == 1
 
 
+def test_hybrid_stack_argument_checks(lib):
+    # chunk size per reuse group: the table is validated entry by entry, capacities against the smallest entry
+    n, R = 5, 2
+    tab = (C.c_void_p * n)(*[0x1000] * n)
+    chunks = lambda *c: (C.c_int32 * len(c))(*c)
+    p1 = good(chunk=1)                               # capacities sized for chunk 1 hold for every chunk size
+    cp1 = p1.as_c()
+    ws = lib.chunkkv_workspace_bytes_hybrid(C.byref(cp1), n, R, chunks(10, 1, 5))
+    assert ws >= max(pkg.chunkkv_workspace_bytes(good(chunk=c, sel_cap=p1.sel_cap, score_cap=p1.score_cap), n, R)
+                     for c in (10, 1, 5))
+    call = lambda cp, table, wsb=ws, q=tab: lib.chunkkv_compress_stack_hybrid(
+        C.byref(cp), n, R, table, q, tab, tab, None, tab, tab, FAKE, FAKE, FAKE, FAKE, wsb, None)
+    assert call(cp1, None) == 1
+    assert call(cp1, chunks(10, 0, 5)) == 2
+    assert call(cp1, chunks(10, -3, 5)) == 2
+    assert call(cp1, chunks(10, 1, 5), wsb=ws - 1) == 4
+    assert call(cp1, chunks(10, 1, 5), q=None) == 1
+    assert lib.chunkkv_workspace_bytes_hybrid(C.byref(cp1), n, R, chunks(10, 0, 5)) == 0
+    assert lib.chunkkv_workspace_bytes_hybrid(C.byref(cp1), n, R, None) == 0
+    # capacities sized for chunk 10 are too small for a group of chunk 1
+    cp10 = good().as_c()
+    assert call(cp10, chunks(10, 1, 5)) == 2
+    assert call(cp10, chunks(10, 20, 10), wsb=1 << 40, q=None) == 1    # ... but fine for chunk sizes >= 10
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         pkg.load_library(str(tmp_path / "nope.so"))
