@@ -225,6 +225,27 @@ int chunkkv_decode_attention(const chunkkv_problem *prob, int32_t compacted, con
                              const void *k, const void *v, float *out, float *lse, void *workspace,
                              size_t workspace_bytes, void *stream);
 
+/* Quality of one compressed layer against the full one: the two diagnostics Appendix A.1 tabulates per
+ * layer.  The paper names them without formulas; this library computes
+ *   l1_loss[b]     = sum |X - X~| / sum |X| over all K and V entries of sequence b, X~ being the cache with the
+ *                    dropped tokens zeroed: the share of the cache's absolute mass held by dropped tokens
+ *                    (0 when everything is kept);
+ *   attn_cos[b][i] = cosine between the attention distribution of decoding query i over all L tokens and its
+ *                    distribution over the kept tokens (placed at their positions, zero elsewhere);
+ *                    average over i for the per-layer figure.
+ * Inputs are a layer's full cache and the output chunkkv_compact / chunkkv_compress_stack wrote for it.
+ *   kv_len     NULL, or as in chunkkv_decode_attention (whole-chunk mode: sel_count-derived token counts)
+ *   q          device [B][Hq][d], the decoding query
+ *   k, v       the full cache (kv_* geometry); k_out, v_out the compacted cache (out_* geometry)
+ *   l1_loss    device float [B]; attn_cos device float [B][Hq]
+ *   workspace  chunkkv_quality_workspace_bytes(prob) bytes (0 = invalid problem)
+ * Cost: both caches are read twice (once by decode attention at twice the softmax scale, whose log-sum-exps
+ * give the cosine, once by the absolute-mass reduction).  Errors as for chunkkv_decode_attention.            */
+size_t chunkkv_quality_workspace_bytes(const chunkkv_problem *prob);
+int chunkkv_quality_metrics(const chunkkv_problem *prob, const int32_t *kv_len, const void *q, const void *k,
+                            const void *v, const void *k_out, const void *v_out, float *l1_loss, float *attn_cos,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* chunkkv_decode_attention for callers that cannot allocate device memory or pass a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and
  * errors as chunkkv_decode_attention, without the workspace: the partial results of the key ranges live in a

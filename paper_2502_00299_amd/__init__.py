@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     chunkkv_chunk_topk,
     chunkkv_compact,
     chunkkv_compress_layer,
+    chunkkv_quality_metrics,
+    chunkkv_quality_workspace_bytes,
     chunkkv_compress_stack_hybrid,
     chunkkv_workspace_bytes_hybrid,
     chunkkv_compress_stack,

@@ -22,7 +22,7 @@ FLAG_WHOLE_CHUNKS, FLAG_TWO_PASS = 1, 2     # chunkkv_problem.flags
 SYMBOLS = ("chunkkv_status_string", "chunkkv_workspace_bytes", "chunkkv_score", "chunkkv_chunk_topk",
            "chunkkv_compact", "chunkkv_compress_stack", "chunkkv_score_lse", "chunkkv_compress_stack_lse",
            "chunkkv_compress_layer", "chunkkv_workspace_bytes_hybrid", "chunkkv_compress_stack_hybrid", "chunkkv_jaccard", "chunkkv_decode_workspace_bytes", "chunkkv_decode_attention",
-           "chunkkv_decode_attention_static",
+           "chunkkv_decode_attention_static", "chunkkv_quality_workspace_bytes", "chunkkv_quality_metrics",
            "chunkkv_timing_begin",
            "chunkkv_timing_end")
 TIMING_KINDS = ("score_stats", "stats_merge", "score_colsum", "chunk_sums", "chunk_topk", "compact", "decode")
@@ -165,6 +165,10 @@ def load_library(path: Optional[str] = None):
     lib.chunkkv_decode_attention.restype = C.c_int
     lib.chunkkv_decode_attention.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, vp, vp, vp, f32p, f32p, vp,
                                              C.c_size_t, vp]
+    lib.chunkkv_quality_workspace_bytes.restype = C.c_size_t
+    lib.chunkkv_quality_workspace_bytes.argtypes = [C.POINTER(_CProblem)]
+    lib.chunkkv_quality_metrics.restype = C.c_int
+    lib.chunkkv_quality_metrics.argtypes = [C.POINTER(_CProblem), i32p, vp, vp, vp, vp, vp, f32p, f32p, vp, C.c_size_t, vp]
     lib.chunkkv_decode_attention_static.restype = C.c_int
     lib.chunkkv_decode_attention_static.argtypes = [C.POINTER(_CProblem), C.c_int32, i32p, vp, vp, vp, f32p, f32p, vp]
     _lib = lib
@@ -295,6 +299,18 @@ def chunkkv_jaccard(prob: Problem, n_groups: int, sel_chunk, sel_len, sel_count,
     cp = prob.as_c()
     _check(load_library().chunkkv_jaccard(C.byref(cp), n_groups, _ptr(sel_chunk), _ptr(sel_len), _ptr(sel_count),
                                           _ptr(jaccard), _stream(stream)), "chunkkv_jaccard")
+
+
+def chunkkv_quality_workspace_bytes(prob: Problem) -> int:
+    return int(load_library().chunkkv_quality_workspace_bytes(C.byref(prob.as_c())))
+
+
+def chunkkv_quality_metrics(prob: Problem, kv_len, q, k, v, k_out, v_out, l1_loss, attn_cos, workspace, stream=None) -> None:
+    cp = prob.as_c()
+    _check(load_library().chunkkv_quality_metrics(
+        C.byref(cp), _ptr(kv_len), _ptr(q), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out), _ptr(l1_loss), _ptr(attn_cos),
+        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
+        "chunkkv_quality_metrics")
 
 
 def chunkkv_decode_workspace_bytes(prob: Problem, compacted: bool = True) -> int:

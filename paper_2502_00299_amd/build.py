@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libchunkkv.so")
-SOURCES = ["api.hip", "compact.hip", "decode.hip", "topk.hip", "score_misc.hip", "score_bf16.hip", "score_f32.hip", "score_f16.hip",
+SOURCES = ["api.hip", "compact.hip", "decode.hip", "quality.hip", "topk.hip", "score_misc.hip", "score_bf16.hip", "score_f32.hip", "score_f16.hip",
            "score_single_bf16.hip", "score_single_f16.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -680,6 +680,91 @@ int chunkkv_decode_attention_static(const chunkkv_problem *prob, int32_t compact
   return chunkkv_decode_attention(prob, compacted, kv_len, q, k, v, out, lse, ws, pl.total, stream);
 }
 
+// Workspace of chunkkv_quality_metrics: the decode workspace (the larger of the two caches' needs), one decode
+// output, two log-sum-exp arrays and the block partials of the two absolute masses.
+namespace {
+struct QualityPlan {
+  int blocks_full, blocks_kept;
+  size_t off_decode, off_out, off_lse_full, off_lse_kept, off_part_full, off_part_kept, total, decode_bytes;
+};
+int quality_plan(const chunkkv_problem *p, QualityPlan *q) {
+  DecodePlan df, dk;
+  int rc;
+  if ((rc = decode_plan(p, false, &df)) || (rc = decode_plan(p, true, &dk))) return rc;
+  int full_max = 0, kept_max = 0;
+  for (int b = 0; b < p->batch; ++b) {
+    full_max = p->seqlen[b] > full_max ? p->seqlen[b] : full_max;
+    kept_max = p->n_keep[b] + p->window > kept_max ? p->n_keep[b] + p->window : kept_max;
+  }
+  q->blocks_full = abs_sum_blocks(full_max);
+  q->blocks_kept = abs_sum_blocks(kept_max);
+  const size_t heads = (size_t)p->batch * p->n_q_heads, kvh = (size_t)p->batch * p->n_kv_heads;
+  q->decode_bytes = df.total > dk.total ? df.total : dk.total;
+  size_t off = 0;
+  q->off_decode = off;    off += align256(q->decode_bytes);
+  q->off_out = off;       off += align256(heads * p->head_dim * sizeof(float));
+  q->off_lse_full = off;  off += align256(heads * sizeof(float));
+  q->off_lse_kept = off;  off += align256(heads * sizeof(float));
+  q->off_part_full = off; off += align256(kvh * q->blocks_full * sizeof(float));
+  q->off_part_kept = off; off += align256(kvh * q->blocks_kept * sizeof(float));
+  q->total = off;
+  return CHUNKKV_OK;
+}
+}  // namespace
+
+size_t chunkkv_quality_workspace_bytes(const chunkkv_problem *prob) {
+  QualityPlan q;
+  if (check_problem(prob, true) || quality_plan(prob, &q)) return 0;
+  return q.total;
+}
+
+int chunkkv_quality_metrics(const chunkkv_problem *prob, const int32_t *kv_len, const void *q, const void *k,
+                            const void *v, const void *k_out, const void *v_out, float *l1_loss, float *attn_cos,
+                            void *workspace, size_t workspace_bytes, void *stream) {
+  int rc = check_problem(prob, true);
+  if (rc) return rc;
+  if (!q || !k || !v || !k_out || !v_out || !l1_loss || !attn_cos) return CHUNKKV_ERR_NULL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(k_out) || misaligned(v_out)) return CHUNKKV_ERR_SHAPE;
+  QualityPlan pl;
+  if ((rc = quality_plan(prob, &pl))) return rc;
+  if (!workspace || workspace_bytes < pl.total) return CHUNKKV_ERR_WORKSPACE;
+  char *ws = (char *)workspace;
+  hipStream_t s = (hipStream_t)stream;
+  // attention statistics at twice the softmax scale: exp(lse) = sum_t exp(2 scale q . k_t)
+  chunkkv_problem twice = *prob;
+  twice.softmax_scale = 2.f * (prob->softmax_scale > 0.f ? prob->softmax_scale : 1.0f / sqrtf((float)prob->head_dim));
+  float *out = (float *)(ws + pl.off_out);
+  float *lse_full = (float *)(ws + pl.off_lse_full), *lse_kept = (float *)(ws + pl.off_lse_kept);
+  rc = chunkkv_decode_attention(&twice, 0, nullptr, q, k, v, out, lse_full, ws + pl.off_decode, pl.decode_bytes, stream);
+  if (rc) return rc;
+  rc = chunkkv_decode_attention(&twice, 1, kv_len, q, k_out, v_out, out, lse_kept, ws + pl.off_decode, pl.decode_bytes, stream);
+  if (rc) return rc;
+  for (int which = 0; which < 2; ++which) {
+    for (int b0 = 0; b0 < prob->batch; b0 += kMaxBatchPerLaunch) {
+      const int nb = prob->batch - b0 < kMaxBatchPerLaunch ? prob->batch - b0 : kMaxBatchPerLaunch;
+      AbsSumArgs a{};
+      a.k = which ? k_out : k; a.v = which ? v_out : v;
+      a.partial = (float *)(ws + (which ? pl.off_part_kept : pl.off_part_full));
+      a.kv_len = which ? kv_len : nullptr;
+      for (int i = 0; i < nb; ++i) {
+        a.n_tok[i] = which ? prob->n_keep[b0 + i] + prob->window : prob->seqlen[b0 + i];
+        a.base[i] = which ? prob->out_base[b0 + i] : prob->kv_base[b0 + i];
+      }
+      a.stride_head = which ? prob->out_stride_head : prob->kv_stride_head;
+      a.stride_tok = which ? prob->out_stride_tok : prob->kv_stride_tok;
+      a.batch0 = b0; a.n_kv_heads = prob->n_kv_heads; a.head_dim = prob->head_dim;
+      a.n_blocks = which ? pl.blocks_kept : pl.blocks_full;
+      if ((rc = launch_abs_sum(prob->dtype, a, nb, s))) return rc;
+    }
+  }
+  QualityFinishArgs f{};
+  f.partial_full = (const float *)(ws + pl.off_part_full); f.partial_kept = (const float *)(ws + pl.off_part_kept);
+  f.lse_full = lse_full; f.lse_kept = lse_kept; f.l1_loss = l1_loss; f.attn_cos = attn_cos;
+  f.n_q_heads = prob->n_q_heads; f.n_kv_heads = prob->n_kv_heads;
+  f.blocks_full = pl.blocks_full; f.blocks_kept = pl.blocks_kept;
+  return launch_quality_finish(f, prob->batch, s);
+}
+
 int chunkkv_timing_begin(int32_t max_records) {
   if (g_timing.on || max_records < 1) return CHUNKKV_ERR_SHAPE;
   hipEvent_t *ev = new hipEvent_t[2 * (size_t)max_records];

@@ -100,6 +100,24 @@ struct DecodeArgs {
   int32_t n_split, rows_per_split;
 };
 
+// Absolute mass of one layer's cache (quality.hip): sum of |K| + |V| over blocks of rows of every (sequence, kv-head).
+struct AbsSumArgs {
+  const void *k, *v;
+  float *partial;             // [batch_total][Hkv][n_blocks]; blocks past a head's rows hold 0
+  const int32_t *kv_len;      // as in DecodeArgs
+  int32_t n_tok[kMaxBatchPerLaunch];
+  int64_t base[kMaxBatchPerLaunch];
+  int64_t stride_head, stride_tok;
+  int32_t batch0, n_kv_heads, head_dim, n_blocks;
+};
+
+struct QualityFinishArgs {
+  const float *partial_full, *partial_kept;   // [B][Hkv][blocks_full], [B][Hkv][blocks_kept]
+  const float *lse_full, *lse_kept;           // [B][Hq]: decode log-sum-exps at twice the softmax scale
+  float *l1_loss, *attn_cos;                  // [B], [B][Hq]
+  int32_t n_q_heads, n_kv_heads, blocks_full, blocks_kept;
+};
+
 // query heads of one kv-head that a decode workgroup serves: 1, 2, 4 or 8 (fp32 caches: at most 4, registers)
 inline int decode_heads_per_wg(int dtype, int g) {
   const int G = g > 4 ? 8 : (g > 2 ? 4 : g);  // 5..7 heads: one padded batch of 8, not two passes over K and V
@@ -150,6 +168,9 @@ int launch_single_scores(const ScoreArgs &a, int n_leaders_slice, int batch_slic
 bool single_pass_ok(int dtype, int head_dim, int rows, int chunk);
 int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s);
 int launch_decode(int dtype, int head_dim, const DecodeArgs &a, int batch_slice, hipStream_t s);
+int abs_sum_blocks(int n_tok_max);
+int launch_abs_sum(int dtype, const AbsSumArgs &a, int batch_slice, hipStream_t s);
+int launch_quality_finish(const QualityFinishArgs &a, int batch, hipStream_t s);
 int launch_compact(int row_bytes, const CompactArgs &a, int n_layers_slice, int batch_slice,
                    int max_entries, hipStream_t s);
 

@@ -208,6 +208,20 @@ def test_hybrid_stack_argument_checks(lib):
     assert call(cp10, chunks(10, 20, 10), wsb=1 << 40, q=None) == 1    # ... but fine for chunk sizes >= 10
 
 
+def test_quality_metrics_argument_checks(lib):
+    p = good()
+    cp = p.as_c()
+    ws = pkg.chunkkv_quality_workspace_bytes(p)
+    assert ws >= max(pkg.chunkkv_decode_workspace_bytes(p, True), pkg.chunkkv_decode_workspace_bytes(p, False))
+    call = lambda q=FAKE, k=FAKE, ko=FAKE, l1=FAKE, cos=FAKE, wsb=ws: lib.chunkkv_quality_metrics(
+        C.byref(cp), None, q, k, FAKE, ko, FAKE, l1, cos, FAKE, wsb, None)
+    assert call(q=None) == 1 and call(k=None) == 1 and call(ko=None) == 1 and call(l1=None) == 1 and call(cos=None) == 1
+    assert call(k=C.c_void_p(0x1004)) == 2
+    assert call(wsb=ws - 1) == 4
+    bad = good(out_base=[0], out_stride_head=848 * 128, out_stride_tok=100)
+    assert pkg.chunkkv_quality_workspace_bytes(bad) == 0
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         pkg.load_library(str(tmp_path / "nope.so"))
