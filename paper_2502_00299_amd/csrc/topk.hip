@@ -7,7 +7,8 @@
 // m = ceil(n_keep / c); if the ragged last chunk is among those m and leaves the budget short, one
 // more chunk is taken.  The lowest-ranked selected chunk is cut to the tokens still missing.
 // Entries are emitted in ascending chunk order with a block-wide prefix scan; their exclusive token
-// offsets are written next to them for the compaction kernel.
+// offsets are written next to them for the compaction kernel.  Up to 16384 chunks per head the scores are
+// read from global memory once and live in registers as keys.
 #include "internal.h"
 
 namespace ckv {
@@ -43,6 +44,12 @@ __device__ __forceinline__ int block_exscan(int x, int *s_tmp, int *total) {
   return wave_base + inc - x;
 }
 
+constexpr int kRegKeys = 16;   // REG: a thread keeps its (at most 16) consecutive chunks' keys in registers
+
+// Thread t owns the K = ceil(C / 1024) consecutive chunks from t * K on, so thread order is chunk order and one
+// pair of block-wide scans emits the whole selection.  REG (C <= 16384, every configuration of the paper at
+// 128K tokens with c >= 8): the scores are read from global memory once; otherwise each step re-reads them.
+template <bool REG>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
   const int tid = threadIdx.x;
   const int bl = blockIdx.x / a.n_kv_heads, h = blockIdx.x % a.n_kv_heads, group = a.group0 + blockIdx.y;
@@ -72,22 +79,57 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
   __shared__ int s_remaining;
   __shared__ int s_pos_trunc;
 
+  const int K = (C + kTopkThreads - 1) / kTopkThreads;
+  const int first = tid * K, last = first + K < C ? first + K : C;   // own chunks: [first, last), may be empty
+  uint32_t kreg[REG ? kRegKeys : 1];
+  if constexpr (REG) {
+#pragma unroll
+    for (int j = 0; j < kRegKeys; ++j) kreg[j] = first + j < last ? order_key(scores[first + j]) : 0u;
+  }
+  // f(chunk index, key) for every own chunk, in index order
+  auto each = [&](auto f) __attribute__((always_inline)) {
+    if constexpr (REG) {
+#pragma unroll
+      for (int j = 0; j < kRegKeys; ++j)
+        if (first + j < last) f(first + j, kreg[j]);
+    } else {
+      for (int i = first; i < last; ++i) f(i, order_key(scores[i]));
+    }
+  };
+
+  // Bits the keys of this head have in common (scores of one head share sign and most of the exponent): the
+  // radix select starts at the first bit that differs, so its first digit already spreads the keys over the
+  // histogram (few same-bin LDS atomics) and there are usually three passes, not four.
+  uint32_t kmn = 0xFFFFFFFFu, kmx = 0u;
+  each([&](int, uint32_t key) { kmn = key < kmn ? key : kmn; kmx = key > kmx ? key : kmx; });
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t x = __shfl_xor(kmn, o), y = __shfl_xor(kmx, o);
+    kmn = x < kmn ? x : kmn; kmx = y > kmx ? y : kmx;
+  }
+  __shared__ uint32_t s_mn[kTopkThreads / 64], s_mx[kTopkThreads / 64];
+  if ((tid & 63) == 0) { s_mn[tid >> 6] = kmn; s_mx[tid >> 6] = kmx; }
+  __syncthreads();
+  for (int i = 0; i < kTopkThreads / 64; ++i) { kmn = s_mn[i] < kmn ? s_mn[i] : kmn; kmx = s_mx[i] > kmx ? s_mx[i] : kmx; }
+  const int hi = kmn == kmx ? 0 : 32 - __builtin_clz(kmn ^ kmx);   // bits [0, hi) vary
+  const uint32_t common = hi >= 32 ? 0u : (kmx >> hi) << hi;
+
   uint32_t thr = 0;   // key of the lowest-ranked selected chunk
   int need = 0;       // how many chunks with key == thr are selected (lowest indices first)
-  int m = m0, total = 0;
+  int m = m0, total = 0, eq_own = 0;
   bool tail_sel = false;
+  const uint32_t tail_key = order_key(scores[C - 1]);
   for (int attempt = 0; attempt < 2; ++attempt) {
-    // ---- radix select: the m-th largest key
-    if (tid == 0) { s_prefix = 0; s_remaining = m; }
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    // ---- radix select: the m-th largest key, 8 bits per pass from bit `top` down
+    if (tid == 0) { s_prefix = common; s_remaining = m; }
+    for (int top = hi; top > 0;) {
+      const int shift = top > 8 ? top - 8 : 0;
       if (tid < 256) s_hist[tid] = 0;
       __syncthreads();
       const uint32_t prefix = s_prefix;
-      const uint32_t mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-      for (int i = tid; i < C; i += kTopkThreads) {
-        const uint32_t key = order_key(scores[i]);
+      const uint32_t mask = top >= 32 ? 0u : (0xFFFFFFFFu << top);   // bits settled so far; prefix is zero below
+      each([&](int, uint32_t key) {
         if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1);
-      }
+      });
       __syncthreads();
       if (tid < 64) {
         // lane l owns digits 255-4l .. 252-4l (descending); find where the running count reaches `remaining`
@@ -103,6 +145,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
         if (before < rem && inc >= rem) {
           for (int j = 0; j < 4; ++j) {
             if (before + v[j] >= rem) {
+              // with fewer than 8 varying bits left the digit's upper bits repeat bits of the prefix
               s_prefix = prefix | ((uint32_t)(255 - 4 * tid - j) << shift);
               s_remaining = rem - before;
               break;
@@ -112,6 +155,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
         }
       }
       __syncthreads();
+      top = shift;
     }
     thr = s_prefix;
     need = s_remaining;  // rank of the threshold chunk among the chunks with key == thr, 1-based
@@ -119,12 +163,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
     // equal keys it is taken last: selected iff key > thr, or key == thr and every equal key is taken.
     if (tid < 256) s_hist[tid] = 0;
     __syncthreads();
-    int eq = 0;
-    for (int i = tid; i < C; i += kTopkThreads) eq += order_key(scores[i]) == thr;
-    if (eq) atomicAdd(&s_hist[0], eq);
+    eq_own = 0;
+    each([&](int, uint32_t key) { eq_own += key == thr; });
+    int eq = eq_own;
+    for (int o = 32; o > 0; o >>= 1) eq += __shfl_xor(eq, o);
+    if ((tid & 63) == 0 && eq) atomicAdd(&s_hist[0], eq);
     __syncthreads();
     const int cnt_eq = s_hist[0];
-    const uint32_t tail_key = order_key(scores[C - 1]);
     tail_sel = tail_key > thr || (tail_key == thr && need == cnt_eq);
     total = m * c - (tail_sel ? c - tail_size : 0);
     __syncthreads();
@@ -133,55 +178,35 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
   }
   // The lowest-ranked selected chunk is the need-th (index order) chunk with key == thr.  It is the
   // tail iff the tail's key == thr and the tail is selected.
-  const bool trunc_is_tail = tail_sel && order_key(scores[C - 1]) == thr;
+  const bool trunc_is_tail = tail_sel && tail_key == thr;
   const int size_trunc = trunc_is_tail ? tail_size : c;
   const int len_trunc = a.whole_chunks ? size_trunc : n_keep - (total - size_trunc);
 
-  // ---- emit in ascending chunk order
+  // ---- emit in ascending chunk order: rank among the equal keys, then position among the selected
   if (tid == 0) s_pos_trunc = 0x7FFFFFFF;
-  // A thread takes kPerThread consecutive chunks per round, so a round costs two block-wide scans for
-  // kPerThread * 1024 chunks.
-  constexpr int kPerThread = 4;
-  int base_sel = 0, base_eq = 0;
-  for (int i0 = 0; i0 < C; i0 += kTopkThreads * kPerThread) {
-    const int first = i0 + tid * kPerThread;
-    uint32_t key[kPerThread];
-    int is_eq[kPerThread], n_eq = 0;
-#pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-      const int i = first + j;
-      key[j] = i < C ? order_key(scores[i]) : 0u;
-      is_eq[j] = i < C && key[j] == thr;
-      n_eq += is_eq[j];
+  int tot_eq, tot_sel;
+  const int eq_rank0 = block_exscan(eq_own, s_tmp, &tot_eq);   // equal keys before this thread's chunks
+  int n_sel = 0, eq_rank = eq_rank0;
+  each([&](int, uint32_t key) {
+    const bool is_eq = key == thr;
+    n_sel += key > thr || (is_eq && eq_rank < need);
+    eq_rank += is_eq;
+  });
+  int pos = block_exscan(n_sel, s_tmp, &tot_sel);
+  eq_rank = eq_rank0;
+  each([&](int i, uint32_t key) {
+    const bool is_eq = key == thr;
+    const bool sel = key > thr || (is_eq && eq_rank < need);
+    if (sel && pos < a.sel_cap) {
+      const bool is_trunc = is_eq && eq_rank + 1 == need;  // the need-th equal key in index order
+      sel_chunk[pos] = i;
+      sel_len[pos] = is_trunc ? len_trunc : (i == C - 1 ? tail_size : c);
+      if (is_trunc) s_pos_trunc = pos;
     }
-    int tot_eq, tot_sel;
-    int eq_rank = base_eq + block_exscan(n_eq, s_tmp, &tot_eq);
-    int flag[kPerThread], n_sel = 0;
-#pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-      const int i = first + j;
-      flag[j] = i < C && (key[j] > thr || (is_eq[j] && eq_rank < need));
-      // remember the rank this chunk has among the equal keys, then advance it
-      is_eq[j] = is_eq[j] ? eq_rank + 1 : 0;  // 1-based rank, 0 = not equal
-      eq_rank += is_eq[j] != 0;
-      n_sel += flag[j];
-    }
-    int pos = base_sel + block_exscan(n_sel, s_tmp, &tot_sel);
-#pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-      const int i = first + j;
-      if (flag[j] && pos < a.sel_cap) {
-        const bool is_trunc = is_eq[j] == need;  // the need-th equal key in index order
-        sel_chunk[pos] = i;
-        sel_len[pos] = is_trunc ? len_trunc : (i == C - 1 ? tail_size : c);
-        if (is_trunc) s_pos_trunc = pos;
-      }
-      pos += flag[j];
-    }
-    base_eq += tot_eq;
-    base_sel += tot_sel;
-    __syncthreads();
-  }
+    pos += sel;
+    eq_rank += is_eq;
+  });
+  __syncthreads();
   if (sel_off) {
     const int pos_trunc = s_pos_trunc;
     for (int p = tid; p < m && p < a.sel_cap; p += kTopkThreads)
@@ -193,7 +218,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkArgs a) {
 int launch_topk(const TopkArgs &a, int n_groups, int batch_slice, hipStream_t s) {
   if (n_groups <= 0 || batch_slice <= 0) return CHUNKKV_OK;
   dim3 grid(batch_slice * a.n_kv_heads, n_groups);
-  hipLaunchKernelGGL(topk_kernel, grid, dim3(kTopkThreads), 0, s, a);
+  int c_max = 0;
+  for (int i = 0; i < batch_slice; ++i) {
+    const int C = (a.seq.seqlen[i] - a.window + a.chunk - 1) / a.chunk;
+    c_max = C > c_max ? C : c_max;
+  }
+  if (c_max <= kTopkThreads * kRegKeys) hipLaunchKernelGGL(topk_kernel<true>, grid, dim3(kTopkThreads), 0, s, a);
+  else hipLaunchKernelGGL(topk_kernel<false>, grid, dim3(kTopkThreads), 0, s, a);
   return hipGetLastError() == hipSuccess ? CHUNKKV_OK : CHUNKKV_ERR_LAUNCH;
 }
 
