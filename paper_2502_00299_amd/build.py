@@ -48,5 +48,37 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_sanitizer_check(out_dir: str) -> str:
+    """Builds tests/host_sanitizer_main.cpp against the library's sources with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the HOST pass only (device code is compiled as usual and never runs in that
+    program): api.hip, which holds every argument check and workspace plan, is recompiled with the sanitizers;
+    the kernels' objects are the ones build() made.  Returns the path of the executable."""
+    os.makedirs(out_dir, exist_ok=True)
+    if not all(os.path.exists(os.path.join(OBJ, s.replace(".hip", ".o"))) for s in SOURCES):
+        build(verbose=False)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    api_o = os.path.join(out_dir, "api_san.o")
+    main_o = os.path.join(out_dir, "host_sanitizer_main.o")
+    exe = os.path.join(out_dir, "host_sanitizer_check")
+    clangxx = os.path.join(os.path.dirname(os.path.realpath(HIPCC)), "..", "lib", "llvm", "bin", "clang++")
+    if not os.path.exists(clangxx):
+        clangxx = "/opt/rocm/lib/llvm/bin/clang++"
+    steps = [
+        [HIPCC, *FLAGS, *san, "-c", os.path.join(CSRC, "api.hip"), "-o", api_o],
+        [clangxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+         "-fno-omit-frame-pointer", "-I", os.path.join(ROOT, "include"), "-c",
+         os.path.join(ROOT, "tests", "host_sanitizer_main.cpp"), "-o", main_o],
+        [clangxx, "-fsanitize=address,undefined", "-o", exe, main_o, api_o,
+         *[os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES if s != "api.hip"],
+         "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib"],
+    ]
+    for cmd in steps:
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("host sanitizer build failed:\n" + " ".join(cmd) + "\n" + r.stderr[-4000:])
+    return exe
+
+
 if __name__ == "__main__":
     build()
