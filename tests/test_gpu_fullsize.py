@@ -265,3 +265,58 @@ def test_one_million_tokens_single_head(lib, scoring_path):
     got = H.read_selection(prob, *sel, 0)[0][0]
     d = H.check_selection(got, orc.chunk_topk(o_cs[0], P, wl.chunk, nk), o_cs[0], P, wl.chunk, nk)
     print(f"{d} chunks differ inside the tie band", flush=True)
+
+
+def test_hybrid_chunk_sizes_128k(lib, scoring_path):
+    """chunkkv_compress_stack_hybrid at the long-context shape: 6 layers, R = 2, chunk sizes 10, 1 and 20 (the
+    token-level group has 131008 candidates and 13101 selection entries per head).  Structure and gather for every
+    layer and head, sampled selections against the oracle."""
+    if scoring_path == "two_pass":
+        pytest.skip("chunk size 1 takes the two-pass kernels anyway; run once")
+    wl = W.get_workload("llama8b_128k_stack").with_(n_layers=6)
+    R, N, chunks = 2, 6, [10, 1, 20]
+    print("workload", wl.name, "6 layers R=2 chunk sizes", chunks, flush=True)
+    layers = [W.make_layer(wl, l, DEV) for l in range(N)]
+    prob = H.make_problem(lib, wl.with_(chunk=1), layers[0])          # capacities for the smallest chunk size
+    G, Hk = 3, wl.n_kv_heads
+    sel = (torch.zeros((G, 1, Hk, prob.sel_cap), dtype=torch.int32, device=DEV),
+           torch.zeros((G, 1, Hk, prob.sel_cap), dtype=torch.int32, device=DEV),
+           torch.zeros((G, 1, Hk), dtype=torch.int32, device=DEV))
+    k_out = [torch.zeros(prob.out_elements(), dtype=wl.torch_dtype, device=DEV) for _ in range(N)]
+    v_out = [torch.zeros(prob.out_elements(), dtype=wl.torch_dtype, device=DEV) for _ in range(N)]
+    ws = torch.empty(lib.chunkkv_workspace_bytes_hybrid(prob, N, R, chunks), dtype=torch.uint8, device=DEV)
+    lib.chunkkv_compress_stack_hybrid(prob, R, chunks, [layers[l].q if l % R == 0 else None for l in range(N)],
+                                      [x.k for x in layers], [x.v for x in layers], None, k_out, v_out, *sel, ws)
+    torch.cuda.synchronize()
+    for grp, c in enumerate(chunks):
+        wl_g = wl.with_(chunk=c, n_layers=R)
+        sel_g = tuple(t[grp:grp + 1] for t in sel)
+        check_structure_everywhere(wl_g, prob, sel_g, R)
+        check_gather_everywhere(wl_g, layers[grp * R:(grp + 1) * R], prob, sel_g, k_out[grp * R:(grp + 1) * R],
+                                v_out[grp * R:(grp + 1) * R], R)
+        n = check_sampled_selections(lib, wl_g, layers[grp * R:(grp + 1) * R], prob, sel_g, R, [(0, 0, (3 * grp + 1) % 8)])
+        print(f"group {grp} (c={c}): {n} chunks differ inside the tie band", flush=True)
+
+
+def test_quality_metrics_128k(lib, scoring_path):
+    """chunkkv_quality_metrics on one full-size layer (131072 tokens, 32 / 8 heads, keep 10 %) against the oracle."""
+    if scoring_path == "two_pass":
+        pytest.skip("the metrics do not depend on the scoring path; run once")
+    wl = W.get_workload("llama8b_128k_stack").with_(n_layers=1)
+    layers, prob, sel, k_out, v_out = run_stack(lib, wl, 1)
+    li = layers[0]
+    q_dec = li.q[:, :, -1, :].contiguous()
+    l1 = torch.full((1,), -1.0, dtype=torch.float32, device=DEV)
+    cos = torch.full((1, wl.n_q_heads), -1.0, dtype=torch.float32, device=DEV)
+    qws = torch.empty(lib.chunkkv_quality_workspace_bytes(prob), dtype=torch.uint8, device=DEV)
+    lib.chunkkv_quality_metrics(prob, None, q_dec, li.k, li.v, k_out[0], v_out[0], l1, cos, qws)
+    torch.cuda.synchronize()
+    got = H.read_selection(prob, *sel, 0)
+    _, k, v = H.seq_arrays(wl, li, 0)
+    kept = [orc.kept_token_indices(got[0][h][0], got[0][h][1], wl.seqlens[0], wl.window, wl.chunk) for h in range(wl.n_kv_heads)]
+    l1_ref = orc.kv_l1_loss(k, v, kept)
+    cos_ref = orc.attention_cosine(W.tensor_bits(q_dec[0]), k, kept)
+    print(f"L1 loss {float(l1[0]):.6f} (oracle {l1_ref:.6f}); cosine mean {float(cos.mean()):.6f} (oracle {cos_ref.mean():.6f})",
+          flush=True)
+    assert abs(float(l1[0]) - l1_ref) <= 1e-6
+    assert np.all(np.abs(cos[0].cpu().numpy() - cos_ref) <= 1e-4 * cos_ref)
