@@ -77,7 +77,7 @@ typedef struct {
  *     of a head as the sum of its sel_len entries.  Default (bit clear): exactly n_keep tokens are kept, the
  *     lowest-ranked selected chunk is cut to its leading tokens.
  * CHUNKKV_FLAG_TWO_PASS  score with the general two-pass kernels even where the single-pass kernel applies
- *     (same results to rounding; see chunkkv_score).                                                       */
+ *     (same results to rounding; the two implementations are described above chunkkv_timing_begin).       */
 #define CHUNKKV_FLAG_WHOLE_CHUNKS 1u
 #define CHUNKKV_FLAG_TWO_PASS 2u
 
@@ -218,8 +218,10 @@ int chunkkv_jaccard(const chunkkv_problem *prob, int32_t n_groups, const int32_t
  *   out         device float [B][Hq][d]
  *   lse         device float [B][Hq] or NULL: natural log of the softmax denominator (-inf for 0 tokens)
  *   workspace   device, chunkkv_decode_workspace_bytes(prob, compacted) bytes, contents scratch
- * Products and sums are fp32 (16-bit inputs are exact in fp32).  Asynchronous on `stream`; two launches;
- * no allocation.  Errors as for chunkkv_score.                                                          */
+ * Products and sums are fp32 (16-bit inputs are exact in fp32): an output element differs from the exact value
+ * by about 1e-6 of the largest magnitude in its head's output row (an element near zero is a difference of
+ * large terms, so the error is relative to the row, not to the element); lse to about 1e-6 absolute.
+ * Asynchronous on `stream`; two launches; no allocation.  Errors as for chunkkv_score.                  */
 size_t chunkkv_decode_workspace_bytes(const chunkkv_problem *prob, int32_t compacted);
 int chunkkv_decode_attention(const chunkkv_problem *prob, int32_t compacted, const int32_t *kv_len, const void *q,
                              const void *k, const void *v, float *out, float *lse, void *workspace,
