@@ -99,8 +99,11 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a) {
     };
     // five 1 KB loads in flight: one pass for a chunk of 10 rows of 128 16-bit values (K and V)
     for (int base = lane; base < total; base += 64 * 5) {
-      const u32x4 r0 = *src_of(base), r1 = *src_of(base + 64), r2 = *src_of(base + 128), r3 = *src_of(base + 192);
-      const u32x4 r4 = *src_of(base + 256);
+      // every byte is read once: streaming (non-temporal) loads (measured 2.6 % faster; the same hint on the
+      // stores is 2 % slower)
+      const u32x4 r0 = __builtin_nontemporal_load(src_of(base)), r1 = __builtin_nontemporal_load(src_of(base + 64));
+      const u32x4 r2 = __builtin_nontemporal_load(src_of(base + 128)), r3 = __builtin_nontemporal_load(src_of(base + 192));
+      const u32x4 r4 = __builtin_nontemporal_load(src_of(base + 256));
       *dst_of(base) = r0;
       if (base + 64 < total) *dst_of(base + 64) = r1;
       if (base + 128 < total) *dst_of(base + 128) = r2;

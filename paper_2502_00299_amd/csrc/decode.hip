@@ -173,8 +173,9 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeArgs a) {
     for (int u = 0; u < U; ++u) {
       const int rowv = base + u * RPW + grp;           // V: register u holds row u
       const int rowk = base + (u ^ ub) * RPW + grp;    // K: register u holds row u ^ ub (ub = 0 without the swizzle)
-      kr[u] = *(const u32x4 *)(kbase + (int64_t)(rowk < r1 ? rowk : r1 - 1) * tok);  // r1 >= 1 inside the loop
-      vr[u] = *(const u32x4 *)(vbase + (int64_t)(rowv < r1 ? rowv : r1 - 1) * tok);
+      // every row is read once: streaming (non-temporal) loads
+      kr[u] = __builtin_nontemporal_load((const u32x4 *)(kbase + (int64_t)(rowk < r1 ? rowk : r1 - 1) * tok));  // r1 >= 1 inside the loop
+      vr[u] = __builtin_nontemporal_load((const u32x4 *)(vbase + (int64_t)(rowv < r1 ? rowv : r1 - 1) * tok));
     }
     if constexpr (kScatter) {
       float x[U][G];

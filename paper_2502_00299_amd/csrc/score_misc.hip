@@ -158,6 +158,7 @@ constexpr int kSinglePeriod = 160, kSingleHalf = 80;   // as in the single-pass 
 __global__ __launch_bounds__(256) void single_scores_kernel(ScoreArgs a) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bl = blockIdx.y / a.n_kv_heads, h = blockIdx.y % a.n_kv_heads, z = blockIdx.z;
   const int64_t problem = ((int64_t)(a.leader0 + z) * a.batch_total + (a.batch0 + bl)) * a.n_kv_heads + h;
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(256) void single_scores_kernel(ScoreArgs a) {
       f32x4 v = {0.f, 0.f, 0.f, 0.f};
       for (int row = lane; row < nrows; row += 64) {
         const float wgt = exp2f(mp[row] - s_ref[row]);
-        const u32x3 d = *(const u32x3 *)(src + row * 12);
+        const u32x3 d = __builtin_nontemporal_load((const u32x3 *)(src + row * 12));
         const f32x4 x = {__uint_as_float(d.x << 8), __uint_as_float(__builtin_amdgcn_alignbit(d.y, d.x, 24) << 8),
                          __uint_as_float(__builtin_amdgcn_alignbit(d.z, d.y, 16) << 8), __uint_as_float(d.z & 0xFFFFFF00u)};
         v += x * wgt;
@@ -229,8 +230,8 @@ __global__ __launch_bounds__(256) void single_scores_kernel(ScoreArgs a) {
       float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int row = lane; row < nrows; row += 64) {
         const float wgt = exp2f(mp[row] - s_ref[row]);
-        const uint4 w = *(const uint4 *)(src_lo + row * 16);
-        const uint32_t w4 = *(const uint32_t *)(src_hi + row * 4);
+        const u32x4 w = __builtin_nontemporal_load((const u32x4 *)(src_lo + row * 16));
+        const uint32_t w4 = __builtin_nontemporal_load((const uint32_t *)(src_hi + row * 4));
         uint32_t q[8];
         q[0] = w.x & 0xFFFFFu;
         q[1] = (w.x >> 20) | ((w.y & 0xFFu) << 12);
